@@ -1,0 +1,248 @@
+// Recursive-doubling all-reduce over the virtual ranks (Sec. 3.1, Sec. 4.1): the
+// Theta(log p) method GossipGraD is compared with, plus its one-pass form and a
+// plain copy kernel for bandwidth calibration.
+#pragma clang fp contract(off)
+
+#include "gg_internal.h"
+
+namespace {
+
+struct ar_args {
+  float* g;
+  int64_t stride;
+  gg_range rng;
+  int64_t tiles;
+  int32_t shift;  // 2^k of this round
+  int32_t p;
+  float scale;    // applied after the add when `scaled`
+  int32_t scaled;
+};
+
+__device__ __forceinline__ int64_t item_index(const gg_range& r, int64_t x) {
+  int64_t i = r.lo + x;
+  if (i >= r.gap_at) i += r.gap_len;
+  return i;
+}
+
+template <bool NT, typename V>
+__device__ __forceinline__ V ld(const V* ptr) {
+  if (NT) return __builtin_nontemporal_load(ptr);
+  return *ptr;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void st(V* ptr, V val) {
+  if (NT)
+    __builtin_nontemporal_store(val, ptr);
+  else
+    *ptr = val;
+}
+
+// One round: ranks j and j ^ shift both end with g[j] + g[j ^ shift].  A thread
+// owns the same chunk of both, so the round is in place: 8 B / rank / element.
+template <typename V, int U, bool NT>
+__global__ void __launch_bounds__(256) allreduce_round_kernel(ar_args a) {
+  const int32_t q = blockIdx.y;
+  const int32_t low = a.shift - 1;
+  const int64_t j = ((q & ~low) << 1) | (q & low);
+  const int64_t c = j | a.shift;
+  V* gj = reinterpret_cast<V*>(a.g + j * a.stride);
+  V* gc = reinterpret_cast<V*>(a.g + c * a.stride);
+  const int64_t per_tile = (int64_t)blockDim.x * U;
+  for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+    const int64_t x0 = tile * per_tile + threadIdx.x;
+    V A[U], B[U];
+    int64_t idx[U];
+    bool on[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t x = x0 + (int64_t)u * blockDim.x;
+      on[u] = x < a.rng.count;
+      idx[u] = item_index(a.rng, x);
+      if (on[u]) {
+        A[u] = ld<NT>(gj + idx[u]);
+        B[u] = ld<NT>(gc + idx[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!on[u]) continue;
+      V s = A[u] + B[u];
+      if (a.scaled) s = s * a.scale;
+      st<NT>(gj + idx[u], s);
+      st<NT>(gc + idx[u], s);
+    }
+  }
+}
+
+// Balanced pairwise tree over ranks [r, r + 2^K): the value every rank holds after
+// K recursive-doubling rounds (addition commutes, so the bits agree).
+template <int K, typename V, bool NT>
+struct tree_sum {
+  static __device__ __forceinline__ V run(const float* g, int64_t stride, int64_t i, int64_t r) {
+    const V lo = tree_sum<K - 1, V, NT>::run(g, stride, i, r);
+    const V hi = tree_sum<K - 1, V, NT>::run(g, stride, i, r + (int64_t(1) << (K - 1)));
+    return lo + hi;
+  }
+};
+template <typename V, bool NT>
+struct tree_sum<0, V, NT> {
+  static __device__ __forceinline__ V run(const float* g, int64_t stride, int64_t i, int64_t r) {
+    return ld<NT>(reinterpret_cast<const V*>(g + r * stride) + i);
+  }
+};
+
+// One pass: read the p values of a chunk once, add them in tree order, write the
+// result to every rank: 8 B / rank / element in total instead of 8 B per round.
+template <int K, typename V, bool NT>
+__global__ void __launch_bounds__(256) allreduce_onepass_kernel(ar_args a) {
+  for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+    const int64_t x = tile * blockDim.x + threadIdx.x;
+    if (x >= a.rng.count) continue;
+    const int64_t i = item_index(a.rng, x);
+    V s = tree_sum<K, V, NT>::run(a.g, a.stride, i, 0);
+    if (a.scaled) s = s * a.scale;
+    for (int64_t r = 0; r < (int64_t(1) << K); ++r) st<NT>(reinterpret_cast<V*>(a.g + r * a.stride) + i, s);
+  }
+}
+
+__global__ void __launch_bounds__(256) copy_kernel(v4f* dst, const v4f* src, int64_t count) {
+  const int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += step)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+template <typename V>
+void launch_round(int U, bool nt, const gg_grid& gd, hipStream_t s, const ar_args& a) {
+#define GG_CASE(UU)                                                                            \
+  case UU:                                                                                     \
+    if (nt)                                                                                    \
+      hipLaunchKernelGGL((allreduce_round_kernel<V, UU, true>), gd.grid, gd.block, 0, s, a);   \
+    else                                                                                       \
+      hipLaunchKernelGGL((allreduce_round_kernel<V, UU, false>), gd.grid, gd.block, 0, s, a);  \
+    break;
+  switch (U) {
+    GG_CASE(1)
+    GG_CASE(2)
+    GG_CASE(4)
+    default:
+      GG_CASE(8)
+  }
+#undef GG_CASE
+}
+
+template <typename V>
+void launch_onepass(int K, const gg_grid& gd, hipStream_t s, const ar_args& a) {
+#define GG_CASE(KK)                                                                            \
+  case KK:                                                                                     \
+    hipLaunchKernelGGL((allreduce_onepass_kernel<KK, V, true>), gd.grid, gd.block, 0, s, a);   \
+    break;
+  switch (K) {
+    GG_CASE(1)
+    GG_CASE(2)
+    GG_CASE(3)
+    GG_CASE(4)
+    GG_CASE(5)
+    GG_CASE(6)
+    default:
+      GG_CASE(7)
+  }
+#undef GG_CASE
+}
+
+enum { MAX_ONEPASS_LOG2 = 7 };
+
+// body (16-byte) + edge (scalar) split shared by both forms
+struct split {
+  gg_range body, edge;
+};
+split make_split(const float* g, int64_t stride, int64_t n) {
+  split s;
+  const bool vec_ok = gg_aligned(g, 16) && stride % 4 == 0;
+  const int64_t body_hi = vec_ok ? n / 4 * 4 : 0;
+  s.body = gg_range{0, body_hi / 4, INT64_MAX, 0};
+  s.edge = gg_range{body_hi, n - body_hi, INT64_MAX, 0};
+  return s;
+}
+
+int check(const gg_ctx* ctx, const float* g) {
+  if (!ctx || !g) return GG_ERR_ARG;
+  if (!gg_aligned(g, 4)) return GG_ERR_ALIGN;
+  if (!gg_is_pow2(ctx->cfg.p)) return GG_ERR_NOT_POW2;
+  return gg_check_ctx_device(ctx);
+}
+
+}  // namespace
+
+extern "C" int gg_allreduce_baseline(gg_ctx* ctx, float* g, int32_t average, void* stream) {
+  int rc = check(ctx, g);
+  if (rc != GG_OK) return rc;
+  const int32_t p = ctx->cfg.p;
+  const split sp = make_split(g, ctx->cfg.rank_stride, ctx->cfg.n);
+  const bool nt = ctx->tune.nontemporal != 0;
+  for (int32_t k = 0; k < ctx->L; ++k) {
+    ar_args a;
+    a.g = g;
+    a.stride = ctx->cfg.rank_stride;
+    a.shift = int32_t(1) << k;
+    a.p = p;
+    a.scaled = (average && k == ctx->L - 1) ? 1 : 0;  // scaling the last round's sum is the same
+    a.scale = 1.0f / (float)p;                        // rounding as scaling afterwards
+    if (sp.body.count > 0) {
+      a.rng = sp.body;
+      gg_grid gd = gg_make_grid(ctx, a.rng.count, ctx->tune.chunks, p / 2);
+      a.tiles = gd.tiles;
+      launch_round<v4f>(ctx->tune.chunks, nt, gd, (hipStream_t)stream, a);
+      GG_HIP_TRY(hipGetLastError());
+    }
+    if (sp.edge.count > 0) {
+      a.rng = sp.edge;
+      gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, p / 2);
+      a.tiles = gd.tiles;
+      launch_round<float>(1, nt, gd, (hipStream_t)stream, a);
+      GG_HIP_TRY(hipGetLastError());
+    }
+  }
+  return GG_OK;
+}
+
+extern "C" int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void* stream) {
+  int rc = check(ctx, g);
+  if (rc != GG_OK) return rc;
+  if (ctx->L > MAX_ONEPASS_LOG2) return gg_allreduce_baseline(ctx, g, average, stream);
+  const split sp = make_split(g, ctx->cfg.rank_stride, ctx->cfg.n);
+  ar_args a;
+  a.g = g;
+  a.stride = ctx->cfg.rank_stride;
+  a.shift = 1;
+  a.p = ctx->cfg.p;
+  a.scaled = average ? 1 : 0;
+  a.scale = 1.0f / (float)ctx->cfg.p;
+  if (sp.body.count > 0) {
+    a.rng = sp.body;
+    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1);
+    a.tiles = gd.tiles;
+    launch_onepass<v4f>(ctx->L, gd, (hipStream_t)stream, a);
+    GG_HIP_TRY(hipGetLastError());
+  }
+  if (sp.edge.count > 0) {
+    a.rng = sp.edge;
+    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1);
+    a.tiles = gd.tiles;
+    launch_onepass<float>(ctx->L, gd, (hipStream_t)stream, a);
+    GG_HIP_TRY(hipGetLastError());
+  }
+  return GG_OK;
+}
+
+extern "C" int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream) {
+  if (!dst || !src || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
+  if (!gg_aligned(dst, 16) || !gg_aligned(src, 16)) return GG_ERR_ALIGN;
+  if (nbytes == 0) return GG_OK;
+  const int64_t count = nbytes / 16;
+  int64_t blocks = (count + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (v4f*)dst,
+                     (const v4f*)src, count);
+  GG_HIP_TRY(hipGetLastError());
+  return GG_OK;
+}

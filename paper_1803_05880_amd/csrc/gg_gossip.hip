@@ -1,0 +1,438 @@
+// Fused momentum-SGD update + pairwise model average (Eq. 1-2, Sec. 6) for all
+// virtual ranks in one launch, and the local update alone (Sec. 4.1).
+//
+// Memory-bound streaming kernels: per rank and parameter the step must read
+// w, g, m (12 B) and write w, m (8 B).  One thread owns the same 16-byte chunk of
+// BOTH partners (hypercube) or of a whole partner cycle (dissemination), so the
+// partner's post-update weights never travel through memory: 20 B / rank /
+// parameter in every mode, in place, race-free by construction.
+//
+// Arithmetic is fp32 with every operation rounded on its own; contraction into
+// fused multiply-add is switched off here and on the command line.
+#pragma clang fp contract(off)
+
+#include "gg_internal.h"
+
+namespace {
+
+enum { MODE_SYNC = 0, MODE_STALE = 1, MODE_GRAD = 2 };
+
+struct step_args {
+  float* w;
+  const float* g;
+  float* m;
+  float* wn;              // where new weights go (== w when in place)
+  const uint16_t* sigma;  // device row of the current communicator: virtual -> world rank
+  int64_t stride;         // elements between consecutive ranks
+  gg_range rng;           // work items, in units of the access type V
+  int64_t tiles;          // tiles per grid row
+  int32_t shift;          // 2^k of the current phase
+  int32_t p;
+  float lr, mu;
+};
+
+template <bool NT, typename V>
+__device__ __forceinline__ V ld(const V* ptr) {
+  if (NT) return __builtin_nontemporal_load(ptr);
+  return *ptr;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void st(V* ptr, V val) {
+  if (NT)
+    __builtin_nontemporal_store(val, ptr);
+  else
+    *ptr = val;
+}
+
+__device__ __forceinline__ int64_t item_index(const gg_range& r, int64_t x) {
+  int64_t i = r.lo + x;
+  if (i >= r.gap_at) i += r.gap_len;
+  return i;
+}
+
+// v = mu*m + lr*g ; returns T = w - v.  Three roundings for v, one for T.
+template <typename V>
+__device__ __forceinline__ V local_update(V w, V g, V m, float lr, float mu, V& v) {
+  const V a = m * mu;
+  const V b = g * lr;
+  v = a + b;
+  return w - v;
+}
+
+// ---------------------------------------------------------------- hypercube pairs
+// Grid row q enumerates the p/2 virtual pairs (v, v | shift) with bit k of v clear;
+// the communicator row turns them into world ranks (j, c).
+template <typename V, int MODE, int U, bool NT, bool GUARD>
+__device__ __forceinline__ void pair_tile(const step_args& a, int64_t x0, const V* wj, const V* gj, V* mj,
+                                          const V* wc, const V* gc, V* mc, V* nj, V* nc) {
+  V Wj[U], Gj[U], Mj[U], Wc[U], Gc[U], Mc[U];
+  int64_t idx[U];
+  bool on[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int64_t x = x0 + (int64_t)u * blockDim.x;
+    on[u] = !GUARD || x < a.rng.count;
+    idx[u] = item_index(a.rng, x);
+    if (on[u]) {
+      Wj[u] = ld<NT>(wj + idx[u]);
+      Wc[u] = ld<NT>(wc + idx[u]);
+      Gj[u] = ld<NT>(gj + idx[u]);
+      Gc[u] = ld<NT>(gc + idx[u]);
+      Mj[u] = ld<NT>(mj + idx[u]);
+      Mc[u] = ld<NT>(mc + idx[u]);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (!on[u]) continue;
+    V vj, vc, outj, outc;
+    if (MODE == MODE_GRAD) {
+      const V gbar = (Gj[u] + Gc[u]) * 0.5f;  // addition commutes: both sides see the same bits
+      outj = local_update(Wj[u], gbar, Mj[u], a.lr, a.mu, vj);
+      outc = local_update(Wc[u], gbar, Mc[u], a.lr, a.mu, vc);
+    } else {
+      const V Tj = local_update(Wj[u], Gj[u], Mj[u], a.lr, a.mu, vj);
+      const V Tc = local_update(Wc[u], Gc[u], Mc[u], a.lr, a.mu, vc);
+      if (MODE == MODE_SYNC) {
+        outj = (Tj + Tc) * 0.5f;
+        outc = outj;
+      } else {  // staleness 1: the partner contributes the weights it held on entry
+        outj = (Tj + Wc[u]) * 0.5f;
+        outc = (Tc + Wj[u]) * 0.5f;
+      }
+    }
+    st<NT>(nj + idx[u], outj);
+    st<NT>(nc + idx[u], outc);
+    st<NT>(mj + idx[u], vj);
+    st<NT>(mc + idx[u], vc);
+  }
+}
+
+template <typename V, int MODE, int U, bool NT>
+__global__ void __launch_bounds__(256) gossip_pair_kernel(step_args a) {
+  const int32_t q = blockIdx.y;
+  const int32_t low = a.shift - 1;
+  const int32_t v0 = ((q & ~low) << 1) | (q & low);
+  const int64_t j = a.sigma[v0];
+  const int64_t c = a.sigma[v0 | a.shift];
+  const V* wj = reinterpret_cast<const V*>(a.w + j * a.stride);
+  const V* wc = reinterpret_cast<const V*>(a.w + c * a.stride);
+  const V* gj = reinterpret_cast<const V*>(a.g + j * a.stride);
+  const V* gc = reinterpret_cast<const V*>(a.g + c * a.stride);
+  V* mj = reinterpret_cast<V*>(a.m + j * a.stride);
+  V* mc = reinterpret_cast<V*>(a.m + c * a.stride);
+  V* nj = reinterpret_cast<V*>(a.wn + j * a.stride);
+  V* nc = reinterpret_cast<V*>(a.wn + c * a.stride);
+  const int64_t per_tile = (int64_t)blockDim.x * U;
+  for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+    const int64_t x0 = tile * per_tile + threadIdx.x;
+    if ((tile + 1) * per_tile <= a.rng.count)
+      pair_tile<V, MODE, U, NT, false>(a, x0, wj, gj, mj, wc, gc, mc, nj, nc);
+    else
+      pair_tile<V, MODE, U, NT, true>(a, x0, wj, gj, mj, wc, gc, mc, nj, nc);
+  }
+}
+
+// ------------------------------------------------------------ dissemination cycles
+// At phase k virtual rank v receives from v - 2^k (mod p).  The map splits the
+// ranks into gcd(p, 2^k) cycles v0, v0+2^k, v0+2*2^k, ...; grid row = cycle.  One
+// thread walks its cycle for one chunk and carries the previous rank's
+// contribution in registers, so each rank's w, g, m are read once and written
+// once, in place.  The communicator row sits in LDS (read at every hop).
+template <typename V, bool NT>
+struct rank_regs {
+  V w, g, m;
+};
+
+template <typename V, int MODE, bool NT>
+__global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, int32_t cycle_len) {
+  __shared__ uint16_t s_sigma[GG_MAX_RANKS];
+  for (int32_t i = threadIdx.x; i < a.p; i += blockDim.x) s_sigma[i] = a.sigma[i];
+  __syncthreads();
+  const int32_t v0 = blockIdx.y;
+  const int64_t rank0 = s_sigma[v0];
+  for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+    const int64_t x = tile * blockDim.x + threadIdx.x;
+    if (x >= a.rng.count) continue;
+    const int64_t i = item_index(a.rng, x);
+    auto W = [&](int64_t rank) { return reinterpret_cast<const V*>(a.w + rank * a.stride) + i; };
+    auto G = [&](int64_t rank) { return reinterpret_cast<const V*>(a.g + rank * a.stride) + i; };
+    auto M = [&](int64_t rank) { return reinterpret_cast<V*>(a.m + rank * a.stride) + i; };
+    auto N = [&](int64_t rank) { return reinterpret_cast<V*>(a.wn + rank * a.stride) + i; };
+
+    // first rank of the cycle: its new weights need the LAST rank's contribution
+    rank_regs<V, NT> first;
+    first.w = ld<NT>(W(rank0));
+    first.g = ld<NT>(G(rank0));
+    first.m = ld<NT>(M(rank0));
+    V carry;  // what the previous rank on the walk contributes to the next one
+    V first_T;
+    if (MODE == MODE_GRAD) {
+      carry = first.g;
+    } else {
+      V v;
+      first_T = local_update(first.w, first.g, first.m, a.lr, a.mu, v);
+      st<NT>(M(rank0), v);
+      carry = (MODE == MODE_SYNC) ? first_T : first.w;
+    }
+    int32_t vt = v0 + a.shift;
+    if (vt >= a.p) vt -= a.p;
+    int64_t rank = s_sigma[vt];
+    rank_regs<V, NT> cur;
+    if (cycle_len > 1) {
+      cur.w = ld<NT>(W(rank));
+      cur.g = ld<NT>(G(rank));
+      cur.m = ld<NT>(M(rank));
+    }
+    for (int32_t t = 1; t < cycle_len; ++t) {
+      // fetch the next rank before the current one is finished (two ranks in flight)
+      int32_t vn = vt + a.shift;
+      if (vn >= a.p) vn -= a.p;
+      const int64_t rank_n = s_sigma[vn];
+      rank_regs<V, NT> nxt;
+      if (t + 1 < cycle_len) {
+        nxt.w = ld<NT>(W(rank_n));
+        nxt.g = ld<NT>(G(rank_n));
+        nxt.m = ld<NT>(M(rank_n));
+      }
+      V v, out;
+      if (MODE == MODE_GRAD) {
+        const V gbar = (cur.g + carry) * 0.5f;
+        out = local_update(cur.w, gbar, cur.m, a.lr, a.mu, v);
+        carry = cur.g;
+      } else {
+        const V T = local_update(cur.w, cur.g, cur.m, a.lr, a.mu, v);
+        out = (T + carry) * 0.5f;
+        carry = (MODE == MODE_SYNC) ? T : cur.w;
+      }
+      st<NT>(M(rank), v);
+      st<NT>(N(rank), out);
+      cur = nxt;
+      vt = vn;
+      rank = rank_n;
+    }
+    // close the cycle
+    if (MODE == MODE_GRAD) {
+      V v;
+      const V gbar = (first.g + carry) * 0.5f;
+      const V out = local_update(first.w, gbar, first.m, a.lr, a.mu, v);
+      st<NT>(M(rank0), v);
+      st<NT>(N(rank0), out);
+    } else {
+      st<NT>(N(rank0), (first_T + carry) * 0.5f);
+    }
+  }
+}
+
+// ------------------------------------------------------------------- local update
+template <typename V, int U, bool NT, bool GUARD>
+__device__ __forceinline__ void sgd_tile(const step_args& a, int64_t x0, const V* w, const V* g, V* m, V* n) {
+  V Wr[U], Gr[U], Mr[U];
+  int64_t idx[U];
+  bool on[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int64_t x = x0 + (int64_t)u * blockDim.x;
+    on[u] = !GUARD || x < a.rng.count;
+    idx[u] = item_index(a.rng, x);
+    if (on[u]) {
+      Wr[u] = ld<NT>(w + idx[u]);
+      Gr[u] = ld<NT>(g + idx[u]);
+      Mr[u] = ld<NT>(m + idx[u]);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (!on[u]) continue;
+    V v;
+    const V T = local_update(Wr[u], Gr[u], Mr[u], a.lr, a.mu, v);
+    st<NT>(n + idx[u], T);
+    st<NT>(m + idx[u], v);
+  }
+}
+
+template <typename V, int U, bool NT>
+__global__ void __launch_bounds__(256) sgd_kernel(step_args a) {
+  const int64_t j = blockIdx.y;
+  const V* w = reinterpret_cast<const V*>(a.w + j * a.stride);
+  const V* g = reinterpret_cast<const V*>(a.g + j * a.stride);
+  V* m = reinterpret_cast<V*>(a.m + j * a.stride);
+  V* n = reinterpret_cast<V*>(a.wn + j * a.stride);
+  const int64_t per_tile = (int64_t)blockDim.x * U;
+  for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+    const int64_t x0 = tile * per_tile + threadIdx.x;
+    if ((tile + 1) * per_tile <= a.rng.count)
+      sgd_tile<V, U, NT, false>(a, x0, w, g, m, n);
+    else
+      sgd_tile<V, U, NT, true>(a, x0, w, g, m, n);
+  }
+}
+
+// ------------------------------------------------------------------------ dispatch
+enum { KIND_PAIR = 0, KIND_CYCLE = 1, KIND_SGD = 2 };
+
+template <typename V, int MODE, int U, bool NT>
+void launch_one(int kind, const gg_grid& gd, hipStream_t s, const step_args& a, int32_t cycle_len) {
+  if (kind == KIND_PAIR)
+    hipLaunchKernelGGL((gossip_pair_kernel<V, MODE, U, NT>), gd.grid, gd.block, 0, s, a);
+  else if (kind == KIND_CYCLE)
+    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, NT>), gd.grid, gd.block, 0, s, a, cycle_len);
+  else
+    hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, 0, s, a);
+}
+
+template <typename V, int MODE>
+void launch_mode(int kind, int U, bool nt, const gg_grid& gd, hipStream_t s, const step_args& a, int32_t cl) {
+#define GG_CASE(UU)                                              \
+  case UU:                                                       \
+    if (nt)                                                      \
+      launch_one<V, MODE, UU, true>(kind, gd, s, a, cl);         \
+    else                                                         \
+      launch_one<V, MODE, UU, false>(kind, gd, s, a, cl);        \
+    break;
+  switch (U) {
+    GG_CASE(1)
+    GG_CASE(2)
+    GG_CASE(4)
+    default:
+      GG_CASE(8)
+  }
+#undef GG_CASE
+}
+
+template <typename V>
+void launch_any(int kind, int mode, int U, bool nt, const gg_grid& gd, hipStream_t s, const step_args& a,
+                int32_t cl) {
+  if (mode == MODE_SYNC)
+    launch_mode<V, MODE_SYNC>(kind, U, nt, gd, s, a, cl);
+  else if (mode == MODE_STALE)
+    launch_mode<V, MODE_STALE>(kind, U, nt, gd, s, a, cl);
+  else
+    launch_mode<V, MODE_GRAD>(kind, U, nt, gd, s, a, cl);
+}
+
+int32_t gcd32(int32_t x, int32_t y) {
+  while (y) {
+    const int32_t t = x % y;
+    x = y;
+    y = t;
+  }
+  return x;
+}
+
+// Enqueue one kind of step over the element range [e_lo, e_hi) of every rank: a
+// 16-byte vector launch for the aligned body and, when the range is ragged or the
+// buffers are not 16-byte aligned, one scalar launch for what is left.
+int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, int64_t e_lo, int64_t e_hi, hipStream_t s) {
+  if (e_hi <= e_lo) return GG_OK;
+  const int32_t p = ctx->cfg.p;
+  int64_t rows = p;
+  int32_t cycle_len = 1;
+  if (kind == KIND_PAIR) rows = p / 2;
+  if (kind == KIND_CYCLE) {
+    rows = gcd32(p, a.shift);
+    cycle_len = p / (int32_t)rows;
+  }
+  const bool vec_ok = gg_aligned(a.w, 16) && gg_aligned(a.g, 16) && gg_aligned(a.m, 16) &&
+                      gg_aligned(a.wn, 16) && (a.stride % 4 == 0);
+  int64_t body_lo = e_lo, body_hi = e_lo;  // empty body unless the vector path applies
+  if (vec_ok) {
+    body_lo = (e_lo + 3) / 4 * 4;
+    body_hi = e_hi / 4 * 4;
+    if (body_hi < body_lo) body_hi = body_lo = e_lo;
+  }
+  const bool nt = ctx->tune.nontemporal != 0;
+  if (body_hi > body_lo) {
+    const int U = kind == KIND_CYCLE ? 1 : ctx->tune.chunks;
+    a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
+    gg_grid gd = gg_make_grid(ctx, a.rng.count, U, rows);
+    a.tiles = gd.tiles;
+    launch_any<v4f>(kind, mode, U, nt, gd, s, a, cycle_len);
+    GG_HIP_TRY(hipGetLastError());
+  }
+  const int64_t edge = (body_lo - e_lo) + (e_hi - body_hi);
+  if (edge > 0) {
+    a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
+    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, rows);
+    a.tiles = gd.tiles;
+    launch_any<float>(kind, mode, 1, nt, gd, s, a, cycle_len);
+    GG_HIP_TRY(hipGetLastError());
+  }
+  return GG_OK;
+}
+
+int check_buffers(const gg_ctx* ctx, const float* w, const float* g, const float* m, const float* wn) {
+  if (!ctx || !w || !g || !m) return GG_ERR_ARG;
+  if (!gg_aligned(w, 4) || !gg_aligned(g, 4) || !gg_aligned(m, 4) || (wn && !gg_aligned(wn, 4)))
+    return GG_ERR_ALIGN;
+  if (w == g || w == m || g == m || (wn && (wn == w || wn == g || wn == m))) return GG_ERR_ARG;
+  return GG_OK;
+}
+
+}  // namespace
+
+extern "C" int gg_gossip_step(gg_ctx* ctx, int64_t step, float* w, const float* g, float* m, float* w_next,
+                              const int64_t* seg_offsets, int32_t nseg, void* stream) {
+  int rc = check_buffers(ctx, w, g, m, w_next);
+  if (rc != GG_OK) return rc;
+  if (step < 0 || nseg < 0) return GG_ERR_ARG;
+  if ((nseg > 0) != (seg_offsets != nullptr)) return GG_ERR_ARG;
+  const gg_config& cfg = ctx->cfg;
+  int64_t e_lo = 0, e_hi = cfg.n;
+  if (nseg > 0) {
+    if (seg_offsets[0] < 0 || seg_offsets[nseg] > cfg.n) return GG_ERR_ARG;
+    for (int32_t s = 0; s < nseg; ++s)
+      if (seg_offsets[s] > seg_offsets[s + 1]) return GG_ERR_ARG;
+    e_lo = seg_offsets[0];
+    e_hi = seg_offsets[nseg];
+  }
+  rc = gg_check_ctx_device(ctx);
+  if (rc != GG_OK) return rc;
+
+  const int32_t k = (int32_t)(step % ctx->L);
+  const int32_t r = (int32_t)((step / ctx->L) % ctx->R);
+  step_args a;
+  a.w = w;
+  a.g = g;
+  a.m = m;
+  a.wn = w_next ? w_next : w;
+  a.sigma = ctx->d_sigma + (size_t)r * cfg.p;
+  a.stride = cfg.rank_stride;
+  a.shift = int32_t(1) << k;
+  a.p = cfg.p;
+  a.lr = cfg.lr;
+  a.mu = cfg.momentum;
+  a.tiles = 0;
+  a.rng = gg_range{0, 0, INT64_MAX, 0};
+
+  int kind, mode;
+  if (cfg.avg_mode == GG_AVG_NONE) {
+    kind = KIND_SGD;
+    mode = MODE_SYNC;
+  } else {
+    kind = cfg.topology == GG_TOPO_HYPERCUBE ? KIND_PAIR : KIND_CYCLE;
+    mode = cfg.avg_mode == GG_AVG_GRAD ? MODE_GRAD : (cfg.staleness ? MODE_STALE : MODE_SYNC);
+  }
+  return enqueue_step(ctx, kind, mode, a, e_lo, e_hi, (hipStream_t)stream);
+}
+
+extern "C" int gg_sgd_step(gg_ctx* ctx, float* w, const float* g, float* m, void* stream) {
+  int rc = check_buffers(ctx, w, g, m, nullptr);
+  if (rc != GG_OK) return rc;
+  rc = gg_check_ctx_device(ctx);
+  if (rc != GG_OK) return rc;
+  step_args a;
+  a.w = w;
+  a.g = g;
+  a.m = m;
+  a.wn = w;
+  a.sigma = ctx->d_sigma;
+  a.stride = ctx->cfg.rank_stride;
+  a.shift = 1;
+  a.p = ctx->cfg.p;
+  a.lr = ctx->cfg.lr;
+  a.mu = ctx->cfg.momentum;
+  a.tiles = 0;
+  a.rng = gg_range{0, 0, INT64_MAX, 0};
+  return enqueue_step(ctx, KIND_SGD, MODE_SYNC, a, 0, ctx->cfg.n, (hipStream_t)stream);
+}

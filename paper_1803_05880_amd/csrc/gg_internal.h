@@ -1,0 +1,103 @@
+// Internal declarations shared by the library's translation units (not part of
+// the C ABI).  gfx950 only.
+#ifndef GG_INTERNAL_H_
+#define GG_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "gg.h"
+
+#define GG_HIP_TRY(expr)                      \
+  do {                                        \
+    hipError_t gg_e_ = (expr);                \
+    if (gg_e_ != hipSuccess) {                \
+      (void)hipGetLastError();                \
+      return GG_ERR_HIP;                      \
+    }                                         \
+  } while (0)
+
+// 16-byte vector of four floats: one global_load_dwordx4 / global_store_dwordx4.
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// A run of `count` consecutive work items starting at index `lo` (in units of the
+// kernel's access type), with an optional hole: items at or beyond `gap_at` are
+// shifted up by `gap_len`.  The hole lets one scalar launch cover the ragged
+// head and tail that surround the 16-byte aligned body.
+struct gg_range {
+  int64_t lo;
+  int64_t count;
+  int64_t gap_at;
+  int64_t gap_len;
+};
+
+struct gg_tuning {
+  int32_t threads;        // workgroup size
+  int32_t chunks;         // access-type items per thread per tile: 1, 2, 4, 8
+  int32_t blocks_per_cu;  // 0: one tile per workgroup; >0: grid-stride with this many workgroups per CU
+  int32_t nontemporal;    // 1: streaming (nt) loads and stores
+};
+
+struct gg_ctx {
+  gg_config cfg;
+  int32_t L;       // phases per communicator, ceil(log2 p)
+  int32_t R;       // communicators
+  int device;
+  int num_cus;
+  gg_tuning tune;
+  std::vector<uint16_t> sigma;  // [R][p] virtual rank -> world rank
+  std::vector<uint16_t> inv;    // [R][p] world rank  -> virtual rank
+  uint16_t* d_sigma;            // device copy of sigma
+  // shuffle state
+  int32_t* d_scratch;           // device int32[scratch_cap]
+  int64_t scratch_cap;
+  int64_t* d_offsets;           // device int64[p+1]
+  int64_t* h_offsets_pinned;    // pinned staging for the upload
+  std::vector<int64_t> offsets_cached;
+};
+
+// ---- Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> 4 words.
+// One round: (hi0:lo0) = M0*c0, (hi1:lo1) = M1*c2,
+//            c <- (hi1^c1^k0, lo1, hi0^c3^k1, lo0); key += (W0, W1) between rounds.
+struct gg_u32x4 {
+  uint32_t x, y, z, w;
+};
+
+__host__ __device__ inline gg_u32x4 gg_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2,
+                                                     uint32_t c3, uint32_t k0, uint32_t k1) {
+  const uint32_t kM0 = 0xD2511F53u, kM1 = 0xCD9E8D57u;
+  const uint32_t kW0 = 0x9E3779B9u, kW1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)kM0 * c0;
+    const uint64_t p1 = (uint64_t)kM1 * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += kW0;
+    k1 += kW1;
+  }
+  return gg_u32x4{c0, c1, c2, c3};
+}
+
+enum { GG_TAG_COMM = 1, GG_TAG_SHUF = 2 };
+
+// Validation helpers (gg_ctx.hip)
+int gg_check_ctx_device(const gg_ctx* ctx);
+inline bool gg_is_pow2(int64_t x) { return x >= 1 && (x & (x - 1)) == 0; }
+inline bool gg_aligned(const void* ptr, uintptr_t a) { return ((uintptr_t)ptr % a) == 0; }
+
+// Launch geometry for a streaming kernel over `items` work items per grid row.
+struct gg_grid {
+  dim3 grid;
+  dim3 block;
+  int64_t tiles;  // tiles per row
+};
+gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t rows);
+
+#endif  // GG_INTERNAL_H_

@@ -1,0 +1,222 @@
+// Rotation of sample indices (Sec. 4.5.2, Lemma 1): the ring of used batches and
+// the partner-swap variant.  Integer work only; results are bit-exact.
+#include <string.h>
+
+#include "gg_internal.h"
+
+namespace {
+
+enum { SWAP_THREADS = 1024, SWAP_WAVES = SWAP_THREADS / 64, SLOTS_PER_THREAD = 4 };
+
+struct swap_args {
+  int32_t* idx;
+  int32_t* sel;            // scratch int32[n_total]: flagged slot numbers, per rank, ascending
+  const int64_t* off;      // device int64[p+1]
+  const uint16_t* sigma;   // communicator row
+  int32_t shift;
+  uint32_t step32;
+  uint32_t k0, k1;
+};
+
+// Inclusive prefix sum of one value per lane across the 64-lane wavefront.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t y = __shfl_up(x, d, 64);
+    if (lane >= (uint32_t)d) x += y;
+  }
+  return x;
+}
+
+// Flag the slots of one rank (4 consecutive slots per thread per tile: one Philox
+// block), and write the flagged slot numbers to sel[base ..] in ascending order:
+// per-thread popcount -> wavefront prefix -> prefix over the 16 wave totals in
+// LDS -> ordered scatter.  Returns the number of flagged slots (same in every
+// thread).
+__device__ uint32_t compact_flagged(const swap_args& a, uint32_t rank, int64_t n_r, int32_t* sel_r,
+                                    uint32_t* s_wave, uint32_t* s_total) {
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  uint32_t running = 0;
+  const int64_t per_tile = (int64_t)SWAP_THREADS * SLOTS_PER_THREAD;
+  for (int64_t tile0 = 0; tile0 < n_r; tile0 += per_tile) {
+    const int64_t slot0 = tile0 + (int64_t)tid * SLOTS_PER_THREAD;
+    uint32_t f[4] = {0, 0, 0, 0};
+    if (slot0 < n_r) {
+      const gg_u32x4 o = gg_philox4x32_10((uint32_t)(slot0 >> 2), rank, a.step32, (uint32_t)GG_TAG_SHUF, a.k0, a.k1);
+      f[0] = (o.x >> 29) == 0;
+      f[1] = (o.y >> 29) == 0 && slot0 + 1 < n_r;
+      f[2] = (o.z >> 29) == 0 && slot0 + 2 < n_r;
+      f[3] = (o.w >> 29) == 0 && slot0 + 3 < n_r;
+    }
+    const uint32_t cnt = f[0] + f[1] + f[2] + f[3];
+    const uint32_t incl = wave_inclusive_scan(cnt, lane);
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+      const uint32_t t = lane < SWAP_WAVES ? s_wave[lane] : 0u;
+      const uint32_t ti = wave_inclusive_scan(t, lane);
+      if (lane < SWAP_WAVES) s_wave[lane] = ti - t;  // exclusive offset of each wave
+      if (lane == SWAP_WAVES - 1) *s_total = ti;
+    }
+    __syncthreads();
+    uint32_t pos = running + s_wave[wave] + (incl - cnt);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (f[e]) sel_r[pos++] = (int32_t)(slot0 + e);
+    running += *s_total;
+    __syncthreads();  // s_wave / s_total are rewritten by the next tile
+  }
+  return running;
+}
+
+// One workgroup per partner pair (j, c): compact both ranks' flagged slots, then
+// swap the r-th flagged slot of j with the r-th flagged slot of c.
+__global__ void __launch_bounds__(SWAP_THREADS) partner_swap_kernel(swap_args a) {
+  __shared__ uint32_t s_wave[SWAP_WAVES];
+  __shared__ uint32_t s_total;
+  const int32_t q = blockIdx.x;
+  const int32_t low = a.shift - 1;
+  const int32_t v0 = ((q & ~low) << 1) | (q & low);
+  const uint32_t j = a.sigma[v0];
+  const uint32_t c = a.sigma[v0 | a.shift];
+  const int64_t off_j = a.off[j], off_c = a.off[c];
+  const int64_t n_j = a.off[j + 1] - off_j, n_c = a.off[c + 1] - off_c;
+  int32_t* sel_j = a.sel + off_j;
+  int32_t* sel_c = a.sel + off_c;
+  const uint32_t cnt_j = compact_flagged(a, j, n_j, sel_j, s_wave, &s_total);
+  const uint32_t cnt_c = compact_flagged(a, c, n_c, sel_c, s_wave, &s_total);
+  __syncthreads();  // the sel lists written above are read by other threads below
+  const uint32_t m = cnt_j < cnt_c ? cnt_j : cnt_c;
+  for (uint32_t r = threadIdx.x; r < m; r += SWAP_THREADS) {
+    int32_t* pa = a.idx + off_j + sel_j[r];
+    int32_t* pb = a.idx + off_c + sel_c[r];
+    const int32_t va = *pa, vb = *pb;
+    *pa = vb;
+    *pb = va;
+  }
+}
+
+struct ring_args {
+  int32_t* idx;
+  int32_t* stage;      // scratch int32[p * batch]
+  const int64_t* off;  // device int64[p+1]
+  int64_t step;
+  int32_t batch;
+  int32_t p;
+};
+
+__device__ __forceinline__ int64_t ring_slot(const ring_args& a, int32_t j, int32_t r) {
+  const int64_t n_j = a.off[j + 1] - a.off[j];
+  const int64_t head = ((a.step % n_j) * ((int64_t)a.batch % n_j)) % n_j;  // (step*batch) mod n_j
+  return a.off[j] + (head + r) % n_j;
+}
+
+// Phase 1: every rank's batch at the head of its queue is copied out.
+__global__ void __launch_bounds__(256) ring_gather_kernel(ring_args a) {
+  const int32_t j = blockIdx.y;
+  for (int32_t r = blockIdx.x * blockDim.x + threadIdx.x; r < a.batch; r += gridDim.x * blockDim.x)
+    a.stage[(int64_t)j * a.batch + r] = a.idx[ring_slot(a, j, r)];
+}
+// Phase 2: rank j's freed slots take the batch of rank j-1, in order.
+__global__ void __launch_bounds__(256) ring_scatter_kernel(ring_args a) {
+  const int32_t j = blockIdx.y;
+  const int32_t src = j == 0 ? a.p - 1 : j - 1;
+  for (int32_t r = blockIdx.x * blockDim.x + threadIdx.x; r < a.batch; r += gridDim.x * blockDim.x)
+    a.idx[ring_slot(a, j, r)] = a.stage[(int64_t)src * a.batch + r];
+}
+
+// Make the device copy of rank_offsets current and the scratch large enough.
+int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s) {
+  const int32_t p = ctx->cfg.p;
+  const int64_t n_total = off[p];
+  if (!ctx->d_offsets) {
+    if (hipMalloc((void**)&ctx->d_offsets, (size_t)(p + 1) * sizeof(int64_t)) != hipSuccess ||
+        hipHostMalloc((void**)&ctx->h_offsets_pinned, (size_t)(p + 1) * sizeof(int64_t), hipHostMallocDefault) !=
+            hipSuccess) {
+      (void)hipGetLastError();
+      return GG_ERR_NOMEM;
+    }
+  }
+  if (ctx->offsets_cached.size() != (size_t)(p + 1) ||
+      memcmp(ctx->offsets_cached.data(), off, (size_t)(p + 1) * sizeof(int64_t)) != 0) {
+    // an earlier upload may still be reading the staging buffer
+    GG_HIP_TRY(hipDeviceSynchronize());
+    memcpy(ctx->h_offsets_pinned, off, (size_t)(p + 1) * sizeof(int64_t));
+    GG_HIP_TRY(hipMemcpyAsync(ctx->d_offsets, ctx->h_offsets_pinned, (size_t)(p + 1) * sizeof(int64_t),
+                              hipMemcpyHostToDevice, s));
+    ctx->offsets_cached.assign(off, off + p + 1);
+  }
+  if (n_total > ctx->scratch_cap) {
+    GG_HIP_TRY(hipDeviceSynchronize());
+    if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+    ctx->d_scratch = nullptr;
+    ctx->scratch_cap = 0;
+    if (hipMalloc((void**)&ctx->d_scratch, (size_t)n_total * sizeof(int32_t)) != hipSuccess) {
+      (void)hipGetLastError();
+      return GG_ERR_NOMEM;
+    }
+    ctx->scratch_cap = n_total;
+  }
+  return GG_OK;
+}
+
+}  // namespace
+
+extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx, const int64_t* rank_offsets,
+                          int32_t batch, void* stream) {
+  if (!ctx || !idx || !rank_offsets || step < 0) return GG_ERR_ARG;
+  if (mode != GG_SHUF_PARTNER_SWAP && mode != GG_SHUF_RING) return GG_ERR_ARG;
+  if (!gg_aligned(idx, 4)) return GG_ERR_ALIGN;
+  const int32_t p = ctx->cfg.p;
+  if (rank_offsets[0] != 0) return GG_ERR_ARG;
+  int64_t min_n = INT64_MAX;
+  for (int32_t j = 0; j < p; ++j) {
+    const int64_t n_j = rank_offsets[j + 1] - rank_offsets[j];
+    if (n_j < 0 || n_j > 0x7fffffffLL) return GG_ERR_ARG;
+    if (n_j < min_n) min_n = n_j;
+  }
+  if (rank_offsets[p] > (int64_t(1) << 34)) return GG_ERR_ARG;
+  if (mode == GG_SHUF_PARTNER_SWAP) {
+    if (ctx->cfg.topology != GG_TOPO_HYPERCUBE) return GG_ERR_UNSUPPORTED;  // needs an involution
+  } else {
+    if (batch < 0 || batch > min_n) return GG_ERR_ARG;
+  }
+  int rc = gg_check_ctx_device(ctx);
+  if (rc != GG_OK) return rc;
+  if (rank_offsets[p] == 0) return GG_OK;
+  hipStream_t s = (hipStream_t)stream;
+  rc = prepare(ctx, rank_offsets, s);
+  if (rc != GG_OK) return rc;
+
+  if (mode == GG_SHUF_PARTNER_SWAP) {
+    const int32_t k = (int32_t)(step % ctx->L);
+    const int32_t r = (int32_t)((step / ctx->L) % ctx->R);
+    swap_args a;
+    a.idx = idx;
+    a.sel = ctx->d_scratch;
+    a.off = ctx->d_offsets;
+    a.sigma = ctx->d_sigma + (size_t)r * p;
+    a.shift = int32_t(1) << k;
+    a.step32 = (uint32_t)((uint64_t)step & 0xffffffffu);
+    a.k0 = (uint32_t)ctx->cfg.seed;
+    a.k1 = (uint32_t)(ctx->cfg.seed >> 32);
+    hipLaunchKernelGGL(partner_swap_kernel, dim3(p / 2), dim3(SWAP_THREADS), 0, s, a);
+    GG_HIP_TRY(hipGetLastError());
+  } else {
+    if (batch == 0) return GG_OK;
+    ring_args a;
+    a.idx = idx;
+    a.stage = ctx->d_scratch;
+    a.off = ctx->d_offsets;
+    a.step = step;
+    a.batch = batch;
+    a.p = p;
+    int32_t bx = (batch + 255) / 256;
+    if (bx > 1024) bx = 1024;
+    hipLaunchKernelGGL(ring_gather_kernel, dim3(bx, p), dim3(256), 0, s, a);
+    GG_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(ring_scatter_kernel, dim3(bx, p), dim3(256), 0, s, a);
+    GG_HIP_TRY(hipGetLastError());
+  }
+  return GG_OK;
+}

@@ -1,0 +1,70 @@
+"""GPU parity: recursive-doubling all-reduce (both forms) + SGD against the
+oracle (Sec. 3.1, Sec. 4.1), and the fixed point it shares with gossip."""
+import numpy as np
+import pytest
+import torch
+
+import gg_synth
+import paper_1803_05880_amd as gg
+from oracle import gossip as og
+from parity_util import assert_close_fp32, host_state
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("form", ["baseline", "onepass"])
+@pytest.mark.parametrize("average", [True, False])
+@pytest.mark.parametrize("p,n,stride", [(2, 5, 5), (4, 100_003, 100_004), (8, 262_151, 262_152), (16, 70_001, 70_001),
+                                        (64, 10_000, 10_000), (128, 4_100, 4_100), (256, 1_031, 1_032)])
+def test_allreduce_matches_oracle_bitwise(form, average, p, n, stride):
+    _, G, _ = host_state(p, n, stride, seed=11)
+    G[:, n:] = 5.0
+    ctx = gg.Context(p=p, n=n, rank_stride=stride)
+    g = G.to(DEV)
+    getattr(ctx, "allreduce_" + form)(g, average=average)
+    torch.cuda.synchronize()
+    Go = G[:, :n].numpy().copy()
+    og.allreduce_recursive_doubling(Go, average=average)
+    out = g.cpu()
+    assert assert_close_fp32(out[:, :n].numpy(), Go, "G") == 0
+    assert (out[:, n:] == 5.0).all()
+    ctx.close()
+
+
+def test_allreduce_sgd_step_and_fixed_point_with_gossip():
+    p, n = 8, 300_000
+    W, G, M = host_state(p, n, n, seed=12)
+    ctx = gg.Context(p=p, n=n, lr=0.1, momentum=0.9)
+    w, g, m = W.to(DEV), G.to(DEV), M.to(DEV)
+    Wo, Go, Mo = W.numpy().copy(), G.numpy().copy(), M.numpy().copy()
+    for _ in range(3):
+        g.copy_(G.to(DEV))
+        ctx.allreduce_baseline(g, average=True)
+        ctx.sgd_step(w, g, m)
+        Go[...] = G.numpy()
+        og.allreduce_sgd_step(Wo, Go, Mo, 0.1, 0.9)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy(), Wo) and np.array_equal(m.cpu().numpy(), Mo)
+    # identical ranks: gossip, all-reduce SGD and single-rank SGD coincide bit for bit
+    W1, G1, M1 = host_state(p, n, n, seed=13, identical_ranks=True)
+    wa, ga, ma = W1.to(DEV), G1.to(DEV), M1.to(DEV)
+    wb, gb, mb = W1.to(DEV), G1.to(DEV), M1.to(DEV)
+    for t in range(5):
+        ctx.gossip_step(t, wa, ga, ma)
+        gb.copy_(G1.to(DEV))
+        ctx.allreduce_onepass(gb, average=True)
+        ctx.sgd_step(wb, gb, mb)
+    torch.cuda.synchronize()
+    assert torch.equal(wa, wb) and torch.equal(ma, mb)
+    assert all(torch.equal(wa[0], wa[j]) for j in range(1, p))
+    ctx.close()
+
+
+def test_allreduce_needs_power_of_two():
+    ctx = gg.Context(p=6, n=16, topology=gg.TOPO_DISSEMINATION)
+    g = torch.zeros(6, 16, device=DEV)
+    with pytest.raises(gg.GGError) as e:
+        ctx.allreduce_baseline(g)
+    assert e.value.code == gg.binding.GG_ERR_NOT_POW2
+    ctx.close()
