@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the GossipGraD hot path on one MI355X.
+
+One "step" is one pass of the whole hot path for all p virtual ranks: the
+partner schedule lookup, the fused momentum-SGD update + pairwise model average
+(one launch) and the partner-swap shuffle of the sample indices (one launch).
+Inputs are synthetic and resident in HBM before the timed region starts.
+
+Workload (default): p = 64 virtual ranks x N = 25,557,032 fp32 parameters
+(ResNet50-sized; w, g, m = 19.6 GB), hypercube partners with rotation,
+synchronous model averaging, plus 1,281,167 int32 sample ids block-partitioned
+over the ranks.  The metric is effective HBM GB/s with the algorithmic minimum
+of 20 bytes per rank and parameter (read w, g, m; write w, m).
+
+Prints ONE JSON line.  Also reported in it: the kernel's roofline fraction from
+HIP events, the staleness-1 double-buffer variant, the recursive-doubling
+all-reduce + SGD comparator on the same buffers, a plain copy kernel, and the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BYTES_PER_RANK_PARAM = 20      # read w, g, m + write w, m
+WORKLOADS = {
+    "C4": dict(p=64, n=25_557_032, shuffle_n=1_281_167),
+    "C5": dict(p=128, n=25_557_032, shuffle_n=1_281_167),
+    "C3": dict(p=16, n=25_557_032, shuffle_n=1_281_167),
+    "C2": dict(p=8, n=6_800_000, shuffle_n=1_281_167),
+    "C1": dict(p=4, n=1_048_576, shuffle_n=1_281_167),
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4", choices=sorted(WORKLOADS))
+    ap.add_argument("--stride-pad", type=int, default=0, help="extra elements between ranks (layout knob)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
+    ap.add_argument("--threads", type=int, default=None)
+    ap.add_argument("--chunks", type=int, default=None)
+    ap.add_argument("--blocks-per-cu", type=int, default=None)
+    ap.add_argument("--nontemporal", type=int, default=None)
+    return ap.parse_args()
+
+
+def event_ms(pairs):
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def time_loop(torch, fn, steps, warmup):
+    """Run fn(t) for warmup+steps steps; returns (wall ms/step, per-call event ms list)."""
+    for t in range(warmup):
+        fn(t, None)
+    torch.cuda.synchronize()
+    pairs = []
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        fn(t, pairs)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return wall, pairs
+
+
+def pmc_traffic_bytes(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
+    counter summary, or None when no summary for this workload exists."""
+    path = os.path.join(ROOT, "profiles", "gossip_pair_kernel_%s_pmc.txt" % workload)
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(p, lr, mu):
+    """The oracle as it stands, on a bounded sample: the first n_s parameters of
+    p ranks (fresh draws of the same distributions), a few steps."""
+    import numpy as np
+    from oracle import gossip as og, schedule as sc
+    n_s, budget_s, max_steps = 1_048_576, 12.0, 400
+    rng = np.random.default_rng(0)
+    W = rng.normal(0, 0.05, (p, n_s)).astype(np.float32)
+    G = rng.normal(0, 1e-3, (p, n_s)).astype(np.float32)
+    M = np.zeros_like(W)
+    og.gossip_step(W, G, M, sc.partners(p, 0, p, sc.HYPERCUBE, 0)[1], lr, mu)      # warm-up
+    t0 = time.perf_counter()
+    steps = 0
+    while steps < max_steps and (steps < 2 or time.perf_counter() - t0 < budget_s):
+        steps += 1
+        og.gossip_step(W, G, M, sc.partners(p, 0, p, sc.HYPERCUBE, steps)[1], lr, mu)
+    dt = (time.perf_counter() - t0) / steps
+    return {
+        "value": round(BYTES_PER_RANK_PARAM * p * n_s / dt / 1e9, 3),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "p=%d ranks x first %d params, %d gossip steps, numpy fp32 (single thread); %.3f s/step"
+                  % (p, n_s, steps, dt),
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the virtual ranks share one MI355X's HBM; --gpus %d is not "
+              "supported (run with --gpus 1)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import gg_synth
+    import paper_1803_05880_amd as gg
+
+    if not torch.cuda.is_available():
+        print("no GPU visible: bench.py needs an MI355X", file=sys.stderr)
+        sys.exit(1)
+    wl = WORKLOADS[args.workload]
+    p, n = wl["p"], wl["n"]
+    stride = n + args.stride_pad
+    lr, mu = gg_synth.LR, gg_synth.MOMENTUM
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    W, G, M = gg_synth.make_state(p, n, stride, seed=0, device=dev)
+    off = gg_synth.block_offsets(wl["shuffle_n"], p)
+    idx = gg_synth.make_indices(wl["shuffle_n"], dev)
+    ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=0, lr=lr, momentum=mu)
+    for key, val in ((gg.TUNE_THREADS, args.threads), (gg.TUNE_CHUNKS, args.chunks),
+                     (gg.TUNE_BLOCKS_PER_CU, args.blocks_per_cu), (gg.TUNE_NONTEMPORAL, args.nontemporal)):
+        if val is not None:
+            ctx.set_tuning(key, val)
+    stream = torch.cuda.current_stream()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- headline: gossip step + shuffle
+    def full_step(t, pairs):
+        if pairs is None:
+            ctx.gossip_step(t, W, G, M)
+        else:
+            a, b = ev(), ev()
+            a.record(stream)
+            ctx.gossip_step(t, W, G, M)
+            b.record(stream)
+            pairs.append((a, b))
+        ctx.shuffle(t, gg.SHUF_PARTNER_SWAP, idx, off)
+
+    ms_step, pairs = time_loop(torch, full_step, args.steps, args.warmup)
+    k_ms = event_ms(pairs)
+    k_avg = sum(k_ms) / len(k_ms)
+    algo_bytes = BYTES_PER_RANK_PARAM * p * n
+    value = algo_bytes / (ms_step * 1e-3) / 1e9
+    achieved = algo_bytes / (k_avg * 1e-3) / 1e9
+
+    out = {
+        "metric": "fused gossip+SGD step: effective HBM GB/s and % of MI355X peak (p ranks x N params)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "config": {
+            "workload": "%s: p=%d virtual ranks x N=%d fp32 params (w,g,m %.2f GB), hypercube partners with "
+                        "rotation (R=p), synchronous model average + momentum SGD (lr 0.1, mu 0.9), plus "
+                        "partner-swap shuffle of %d int32 sample ids" % (args.workload, p, n, 12.0 * p * stride / 1e9,
+                                                                         wl["shuffle_n"]),
+            "p": p, "n": n, "rank_stride": stride, "bytes_per_step": algo_bytes,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "gossip_pair_kernel<v4f, sync>",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": pmc_traffic_bytes(args.workload),
+            "algorithmic_bytes_per_launch": algo_bytes,
+            "kernel_ms_avg": round(k_avg, 4),
+            "kernel_ms_min": round(min(k_ms), 4),
+        },
+    }
+
+    if not args.no_extras:
+        extras = {}
+        reps = max(3, min(args.steps, 16))
+
+        # shuffle alone
+        def shuf(t, pairs):
+            a, b = ev(), ev()
+            a.record(stream)
+            ctx.shuffle(t, gg.SHUF_PARTNER_SWAP, idx, off)
+            b.record(stream)
+            if pairs is not None:
+                pairs.append((a, b))
+        _, pr = time_loop(torch, shuf, reps, 2)
+        extras["shuffle_ms"] = round(sum(event_ms(pr)) / len(pr), 4)
+
+        # plain copy kernel on a W-sized buffer (read + write = 2 x bytes)
+        scratch = torch.empty_like(W)
+
+        def cp(t, pairs):
+            a, b = ev(), ev()
+            a.record(stream)
+            gg.copy_probe(scratch, W)
+            b.record(stream)
+            if pairs is not None:
+                pairs.append((a, b))
+        _, pr = time_loop(torch, cp, reps, 2)
+        cp_ms = sum(event_ms(pr)) / len(pr)
+        extras["copy_kernel_GBps"] = round(2.0 * 4 * p * stride / (cp_ms * 1e-3) / 1e9, 1)
+
+        # staleness-1 variant with a double buffer (scratch doubles as the second w)
+        ctx_s = gg.Context(p=p, n=n, rank_stride=stride, seed=0, lr=lr, momentum=mu, staleness=1)
+        bufs = [W, scratch]
+
+        def stale(t, pairs):
+            a, b = ev(), ev()
+            a.record(stream)
+            ctx_s.gossip_step(t, bufs[t & 1], G, M, w_next=bufs[(t & 1) ^ 1])
+            b.record(stream)
+            if pairs is not None:
+                pairs.append((a, b))
+        _, pr = time_loop(torch, stale, reps, 2)
+        st_ms = sum(event_ms(pr)) / len(pr)
+        extras["staleness1_double_buffer"] = {"kernel_ms": round(st_ms, 4),
+                                              "GBps": round(algo_bytes / (st_ms * 1e-3) / 1e9, 1)}
+        ctx_s.close()
+
+        # all-reduce + SGD comparator on the same buffers (G is clobbered: last)
+        L = p.bit_length() - 1
+
+        def ar(t, pairs):
+            a, b = ev(), ev()
+            a.record(stream)
+            ctx.allreduce_baseline(G, average=True)
+            ctx.sgd_step(W, G, M)
+            b.record(stream)
+            if pairs is not None:
+                pairs.append((a, b))
+        _, pr = time_loop(torch, ar, max(3, reps // 2), 1)
+        ar_ms = sum(event_ms(pr)) / len(pr)
+
+        def ar1(t, pairs):
+            a, b = ev(), ev()
+            a.record(stream)
+            ctx.allreduce_onepass(G, average=True)
+            ctx.sgd_step(W, G, M)
+            b.record(stream)
+            if pairs is not None:
+                pairs.append((a, b))
+        _, pr = time_loop(torch, ar1, max(3, reps // 2), 1)
+        ar1_ms = sum(event_ms(pr)) / len(pr)
+        extras["allreduce_sgd"] = {
+            "recursive_doubling_ms": round(ar_ms, 4),
+            "onepass_ms": round(ar1_ms, 4),
+            "gossip_vs_recursive_doubling_time_ratio": round(k_avg / ar_ms, 4),
+            "gossip_vs_onepass_time_ratio": round(k_avg / ar1_ms, 4),
+            "bytes_moved_ratio_message_level": round(1.0 / L, 4),
+            "bytes_moved_ratio_hbm_level": round(20.0 / (8.0 * L + 20.0), 4),
+        }
+        out["extras"] = extras
+    ctx.close()
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(p, lr, mu)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
