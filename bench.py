@@ -45,7 +45,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOADS))
-    ap.add_argument("--stride-pad", type=int, default=0, help="extra elements between ranks (layout knob)")
+    ap.add_argument("--stride-align", type=int, default=1024,
+                    help="rank_stride is N rounded up to a multiple of this many elements (layout choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
     ap.add_argument("--threads", type=int, default=None)
@@ -127,7 +128,7 @@ def main():
         sys.exit(1)
     wl = WORKLOADS[args.workload]
     p, n = wl["p"], wl["n"]
-    stride = n + args.stride_pad
+    stride = (n + args.stride_align - 1) // args.stride_align * args.stride_align
     lr, mu = gg_synth.LR, gg_synth.MOMENTUM
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -187,7 +188,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "gossip_pair_kernel<v4f, sync>",
+            "kernel": "gossip_pair_lean_kernel<MODE_SYNC, nontemporal>",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",

@@ -150,9 +150,12 @@ int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
 int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream);
 
 /* Launch-shape knobs for bandwidth sweeps (never change results).  key:
- *   0 = threads per block (64..1024, multiple of 64), 1 = 16-byte chunks per
- *   thread (1, 2, 4, 8), 2 = workgroups per CU for the grid-stride form (0 = one
- *   tile per workgroup), 3 = non-temporal loads/stores (0/1). */
+ *   0 = threads per workgroup (64, 128 or 256; default 64),
+ *   1 = 16-byte chunks per thread per tile (1, 2, 4, 8; default 1),
+ *   2 = cap on resident workgroups per CU, enforced by reserving LDS
+ *       (0 = no cap, 3..64; default 10: few waves in flight keep the DRAM
+ *       row-buffer working set small, which is what the streaming kernels want),
+ *   3 = non-temporal loads/stores (0/1; default 1). */
 int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value);
 
 /* Static, never NULL. */

@@ -116,9 +116,9 @@ void launch_round(int U, bool nt, const gg_grid& gd, hipStream_t s, const ar_arg
 #define GG_CASE(UU)                                                                            \
   case UU:                                                                                     \
     if (nt)                                                                                    \
-      hipLaunchKernelGGL((allreduce_round_kernel<V, UU, true>), gd.grid, gd.block, 0, s, a);   \
+      hipLaunchKernelGGL((allreduce_round_kernel<V, UU, true>), gd.grid, gd.block, gd.lds_bytes, s, a);   \
     else                                                                                       \
-      hipLaunchKernelGGL((allreduce_round_kernel<V, UU, false>), gd.grid, gd.block, 0, s, a);  \
+      hipLaunchKernelGGL((allreduce_round_kernel<V, UU, false>), gd.grid, gd.block, gd.lds_bytes, s, a);  \
     break;
   switch (U) {
     GG_CASE(1)
@@ -134,7 +134,7 @@ template <typename V>
 void launch_onepass(int K, const gg_grid& gd, hipStream_t s, const ar_args& a) {
 #define GG_CASE(KK)                                                                            \
   case KK:                                                                                     \
-    hipLaunchKernelGGL((allreduce_onepass_kernel<KK, V, true>), gd.grid, gd.block, 0, s, a);   \
+    hipLaunchKernelGGL((allreduce_onepass_kernel<KK, V, true>), gd.grid, gd.block, gd.lds_bytes, s, a);   \
     break;
   switch (K) {
     GG_CASE(1)
@@ -238,10 +238,12 @@ extern "C" int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* s
   if (!dst || !src || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
   if (!gg_aligned(dst, 16) || !gg_aligned(src, 16)) return GG_ERR_ALIGN;
   if (nbytes == 0) return GG_OK;
+  // one wavefront per workgroup, one 16-byte chunk per thread, no occupancy cap: the
+  // shape that copies fastest on this part
   const int64_t count = nbytes / 16;
-  int64_t blocks = (count + 255) / 256;
-  if (blocks > 256 * 16) blocks = 256 * 16;
-  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (v4f*)dst,
+  int64_t blocks = (count + 63) / 64;
+  if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(64), 0, (hipStream_t)stream, (v4f*)dst,
                      (const v4f*)src, count);
   GG_HIP_TRY(hipGetLastError());
   return GG_OK;

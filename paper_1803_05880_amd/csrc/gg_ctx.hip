@@ -55,16 +55,20 @@ gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t r
   const int64_t per_tile = (int64_t)ctx->tune.threads * chunks;
   out.tiles = (items + per_tile - 1) / per_tile;
   int64_t gx = out.tiles;
-  if (ctx->tune.blocks_per_cu > 0) {
-    // grid-stride form: a fixed number of workgroups per CU shared over the rows
-    int64_t want = ((int64_t)ctx->num_cus * ctx->tune.blocks_per_cu + rows - 1) / rows;
-    if (want < 1) want = 1;
-    if (gx > want) gx = want;
-  }
   if (gx > 0x7fffffffLL) gx = 0x7fffffffLL;  // the kernels loop over tiles, any gx works
   if (gx < 1) gx = 1;
   out.grid = dim3((unsigned)gx, (unsigned)rows, 1);
   out.block = dim3((unsigned)ctx->tune.threads, 1, 1);
+  // Occupancy cap: a CU has 160 KB of LDS, so a workgroup that reserves 160 KB / k of
+  // it leaves room for k workgroups.  The streaming kernels run fastest with about
+  // one wavefront per SIMD: more waves in flight widen the window of DRAM rows
+  // touched at once and cost row-buffer hits.
+  out.lds_bytes = 0;
+  if (ctx->tune.blocks_per_cu > 0) {
+    uint32_t b = (uint32_t)(160u * 1024u / (uint32_t)ctx->tune.blocks_per_cu) & ~255u;
+    if (b > 64u * 1024u - 4096u) b = 64u * 1024u - 4096u;  // stay below the default dynamic-LDS limit
+    out.lds_bytes = b;
+  }
   return out;
 }
 
@@ -92,7 +96,7 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
   ctx->scratch_cap = 0;
   ctx->d_offsets = nullptr;
   ctx->h_offsets_pinned = nullptr;
-  ctx->tune = gg_tuning{256, 2, 0, 1};
+  ctx->tune = gg_tuning{64, 1, 10, 1};
 
   const size_t entries = (size_t)ctx->R * (size_t)cfg->p;
   try {
@@ -185,7 +189,7 @@ extern "C" int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value) {
   if (!ctx) return GG_ERR_ARG;
   switch (key) {
     case 0:
-      if (value < 64 || value > 1024 || value % 64) return GG_ERR_ARG;
+      if (value != 64 && value != 128 && value != 256) return GG_ERR_ARG;
       ctx->tune.threads = value;
       return GG_OK;
     case 1:
@@ -193,7 +197,7 @@ extern "C" int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value) {
       ctx->tune.chunks = value;
       return GG_OK;
     case 2:
-      if (value < 0 || value > 64) return GG_ERR_ARG;
+      if (value != 0 && (value < 3 || value > 64)) return GG_ERR_ARG;
       ctx->tune.blocks_per_cu = value;
       return GG_OK;
     case 3:

@@ -31,6 +31,15 @@ struct step_args {
   float lr, mu;
 };
 
+// World ranks (j, c) of the step's pairs, one packed entry per grid row q.  Passed
+// by value so that a workgroup finds its two ranks with one scalar load from the
+// kernel-argument segment, issued together with the other arguments: workgroups
+// here live for a microsecond or two and a dependent table lookup in global
+// memory would be a visible part of that.
+struct pair_table {
+  uint32_t jc[GG_MAX_RANKS / 2];  // j | c << 16
+};
+
 template <bool NT, typename V>
 __device__ __forceinline__ V ld(const V* ptr) {
   if (NT) return __builtin_nontemporal_load(ptr);
@@ -60,8 +69,7 @@ __device__ __forceinline__ V local_update(V w, V g, V m, float lr, float mu, V& 
 }
 
 // ---------------------------------------------------------------- hypercube pairs
-// Grid row q enumerates the p/2 virtual pairs (v, v | shift) with bit k of v clear;
-// the communicator row turns them into world ranks (j, c).
+// Grid row q is one of the p/2 pairs; the host lists their world ranks (j, c).
 template <typename V, int MODE, int U, bool NT, bool GUARD>
 __device__ __forceinline__ void pair_tile(const step_args& a, int64_t x0, const V* wj, const V* gj, V* mj,
                                           const V* wc, const V* gc, V* mc, V* nj, V* nc) {
@@ -109,12 +117,10 @@ __device__ __forceinline__ void pair_tile(const step_args& a, int64_t x0, const 
 }
 
 template <typename V, int MODE, int U, bool NT>
-__global__ void __launch_bounds__(256) gossip_pair_kernel(step_args a) {
-  const int32_t q = blockIdx.y;
-  const int32_t low = a.shift - 1;
-  const int32_t v0 = ((q & ~low) << 1) | (q & low);
-  const int64_t j = a.sigma[v0];
-  const int64_t c = a.sigma[v0 | a.shift];
+__global__ void __launch_bounds__(256) gossip_pair_kernel(step_args a, pair_table pt) {
+  const uint32_t jc = pt.jc[blockIdx.y];
+  const int64_t j = jc & 0xffffu;
+  const int64_t c = jc >> 16;
   const V* wj = reinterpret_cast<const V*>(a.w + j * a.stride);
   const V* wc = reinterpret_cast<const V*>(a.w + c * a.stride);
   const V* gj = reinterpret_cast<const V*>(a.g + j * a.stride);
@@ -124,13 +130,57 @@ __global__ void __launch_bounds__(256) gossip_pair_kernel(step_args a) {
   V* nj = reinterpret_cast<V*>(a.wn + j * a.stride);
   V* nc = reinterpret_cast<V*>(a.wn + c * a.stride);
   const int64_t per_tile = (int64_t)blockDim.x * U;
-  for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+  int64_t tile = blockIdx.x;  // the grid never has more columns than tiles
+  do {
     const int64_t x0 = tile * per_tile + threadIdx.x;
     if ((tile + 1) * per_tile <= a.rng.count)
       pair_tile<V, MODE, U, NT, false>(a, x0, wj, gj, mj, wc, gc, mc, nj, nc);
     else
       pair_tile<V, MODE, U, NT, true>(a, x0, wj, gj, mj, wc, gc, mc, nj, nc);
+    tile += gridDim.x;
+  } while (tile < a.tiles);
+}
+
+// Lean form of the same kernel for the default launch shape: one wavefront per
+// workgroup, one 16-byte chunk per thread, one tile per workgroup, no ragged
+// range.  Workgroups live for about a microsecond, so everything that delays the
+// first load (extra argument fetches, loop set-up) shows up in the bandwidth.
+template <int MODE, bool NT>
+__global__ void __launch_bounds__(64) gossip_pair_lean_kernel(step_args a, pair_table pt) {
+  const uint32_t jc = pt.jc[blockIdx.y];
+  const int64_t j = jc & 0xffffu;
+  const int64_t c = jc >> 16;
+  const int64_t i = a.rng.lo + (int64_t)blockIdx.x * 64 + threadIdx.x;
+  if (i >= a.rng.lo + a.rng.count) return;
+  const v4f* wj = reinterpret_cast<const v4f*>(a.w + j * a.stride) + i;
+  const v4f* wc = reinterpret_cast<const v4f*>(a.w + c * a.stride) + i;
+  const v4f* gj = reinterpret_cast<const v4f*>(a.g + j * a.stride) + i;
+  const v4f* gc = reinterpret_cast<const v4f*>(a.g + c * a.stride) + i;
+  v4f* mj = reinterpret_cast<v4f*>(a.m + j * a.stride) + i;
+  v4f* mc = reinterpret_cast<v4f*>(a.m + c * a.stride) + i;
+  v4f* nj = reinterpret_cast<v4f*>(a.wn + j * a.stride) + i;
+  v4f* nc = reinterpret_cast<v4f*>(a.wn + c * a.stride) + i;
+  const v4f Wj = ld<NT>(wj), Wc = ld<NT>(wc), Gj = ld<NT>(gj), Gc = ld<NT>(gc), Mj = ld<NT>(mj), Mc = ld<NT>(mc);
+  v4f vj, vc, outj, outc;
+  if (MODE == MODE_GRAD) {
+    const v4f gbar = (Gj + Gc) * 0.5f;
+    outj = local_update(Wj, gbar, Mj, a.lr, a.mu, vj);
+    outc = local_update(Wc, gbar, Mc, a.lr, a.mu, vc);
+  } else {
+    const v4f Tj = local_update(Wj, Gj, Mj, a.lr, a.mu, vj);
+    const v4f Tc = local_update(Wc, Gc, Mc, a.lr, a.mu, vc);
+    if (MODE == MODE_SYNC) {
+      outj = (Tj + Tc) * 0.5f;
+      outc = outj;
+    } else {
+      outj = (Tj + Wc) * 0.5f;
+      outc = (Tc + Wj) * 0.5f;
+    }
   }
+  st<NT>(nj, outj);
+  st<NT>(nc, outc);
+  st<NT>(mj, vj);
+  st<NT>(mc, vc);
 }
 
 // ------------------------------------------------------------ dissemination cycles
@@ -271,24 +321,38 @@ __global__ void __launch_bounds__(256) sgd_kernel(step_args a) {
 // ------------------------------------------------------------------------ dispatch
 enum { KIND_PAIR = 0, KIND_CYCLE = 1, KIND_SGD = 2 };
 
+struct launch_ctx {
+  gg_grid gd;
+  hipStream_t s;
+  const pair_table* pt;
+  int32_t cycle_len;
+};
+
 template <typename V, int MODE, int U, bool NT>
-void launch_one(int kind, const gg_grid& gd, hipStream_t s, const step_args& a, int32_t cycle_len) {
-  if (kind == KIND_PAIR)
-    hipLaunchKernelGGL((gossip_pair_kernel<V, MODE, U, NT>), gd.grid, gd.block, 0, s, a);
+void launch_one(int kind, const launch_ctx& lc, const step_args& a) {
+  const gg_grid& gd = lc.gd;
+  hipStream_t s = lc.s;
+  const int32_t cycle_len = lc.cycle_len;
+  if (kind == KIND_PAIR) {
+    if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles)
+      hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, *lc.pt);
+    else
+      hipLaunchKernelGGL((gossip_pair_kernel<V, MODE, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, *lc.pt);
+  }
   else if (kind == KIND_CYCLE)
-    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, NT>), gd.grid, gd.block, 0, s, a, cycle_len);
+    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, cycle_len);
   else
-    hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, 0, s, a);
+    hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a);
 }
 
 template <typename V, int MODE>
-void launch_mode(int kind, int U, bool nt, const gg_grid& gd, hipStream_t s, const step_args& a, int32_t cl) {
+void launch_mode(int kind, int U, bool nt, const launch_ctx& lc, const step_args& a) {
 #define GG_CASE(UU)                                              \
   case UU:                                                       \
     if (nt)                                                      \
-      launch_one<V, MODE, UU, true>(kind, gd, s, a, cl);         \
+      launch_one<V, MODE, UU, true>(kind, lc, a);                \
     else                                                         \
-      launch_one<V, MODE, UU, false>(kind, gd, s, a, cl);        \
+      launch_one<V, MODE, UU, false>(kind, lc, a);               \
     break;
   switch (U) {
     GG_CASE(1)
@@ -301,14 +365,13 @@ void launch_mode(int kind, int U, bool nt, const gg_grid& gd, hipStream_t s, con
 }
 
 template <typename V>
-void launch_any(int kind, int mode, int U, bool nt, const gg_grid& gd, hipStream_t s, const step_args& a,
-                int32_t cl) {
+void launch_any(int kind, int mode, int U, bool nt, const launch_ctx& lc, const step_args& a) {
   if (mode == MODE_SYNC)
-    launch_mode<V, MODE_SYNC>(kind, U, nt, gd, s, a, cl);
+    launch_mode<V, MODE_SYNC>(kind, U, nt, lc, a);
   else if (mode == MODE_STALE)
-    launch_mode<V, MODE_STALE>(kind, U, nt, gd, s, a, cl);
+    launch_mode<V, MODE_STALE>(kind, U, nt, lc, a);
   else
-    launch_mode<V, MODE_GRAD>(kind, U, nt, gd, s, a, cl);
+    launch_mode<V, MODE_GRAD>(kind, U, nt, lc, a);
 }
 
 int32_t gcd32(int32_t x, int32_t y) {
@@ -323,12 +386,23 @@ int32_t gcd32(int32_t x, int32_t y) {
 // Enqueue one kind of step over the element range [e_lo, e_hi) of every rank: a
 // 16-byte vector launch for the aligned body and, when the range is ragged or the
 // buffers are not 16-byte aligned, one scalar launch for what is left.
-int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, int64_t e_lo, int64_t e_hi, hipStream_t s) {
+int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* sigma_host, int64_t e_lo,
+                 int64_t e_hi, hipStream_t s) {
   if (e_hi <= e_lo) return GG_OK;
   const int32_t p = ctx->cfg.p;
   int64_t rows = p;
   int32_t cycle_len = 1;
-  if (kind == KIND_PAIR) rows = p / 2;
+  pair_table pt;
+  if (kind == KIND_PAIR) {
+    rows = p / 2;
+    // virtual pairs (v, v | shift) with bit k of v clear, mapped through the communicator
+    const int32_t low = a.shift - 1;
+    for (int32_t q = 0; q < p / 2; ++q) {
+      const int32_t v0 = ((q & ~low) << 1) | (q & low);
+      pt.jc[q] = (uint32_t)sigma_host[v0] | ((uint32_t)sigma_host[v0 | a.shift] << 16);
+    }
+    for (int32_t q = p / 2; q < GG_MAX_RANKS / 2; ++q) pt.jc[q] = 0;
+  }
   if (kind == KIND_CYCLE) {
     rows = gcd32(p, a.shift);
     cycle_len = p / (int32_t)rows;
@@ -345,17 +419,17 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, int64_t e_lo, int
   if (body_hi > body_lo) {
     const int U = kind == KIND_CYCLE ? 1 : ctx->tune.chunks;
     a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
-    gg_grid gd = gg_make_grid(ctx, a.rng.count, U, rows);
-    a.tiles = gd.tiles;
-    launch_any<v4f>(kind, mode, U, nt, gd, s, a, cycle_len);
+    launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows), s, &pt, cycle_len};
+    a.tiles = lc.gd.tiles;
+    launch_any<v4f>(kind, mode, U, nt, lc, a);
     GG_HIP_TRY(hipGetLastError());
   }
   const int64_t edge = (body_lo - e_lo) + (e_hi - body_hi);
   if (edge > 0) {
     a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
-    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, rows);
-    a.tiles = gd.tiles;
-    launch_any<float>(kind, mode, 1, nt, gd, s, a, cycle_len);
+    launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows), s, &pt, cycle_len};
+    a.tiles = lc.gd.tiles;
+    launch_any<float>(kind, mode, 1, nt, lc, a);
     GG_HIP_TRY(hipGetLastError());
   }
   return GG_OK;
@@ -413,7 +487,7 @@ extern "C" int gg_gossip_step(gg_ctx* ctx, int64_t step, float* w, const float* 
     kind = cfg.topology == GG_TOPO_HYPERCUBE ? KIND_PAIR : KIND_CYCLE;
     mode = cfg.avg_mode == GG_AVG_GRAD ? MODE_GRAD : (cfg.staleness ? MODE_STALE : MODE_SYNC);
   }
-  return enqueue_step(ctx, kind, mode, a, e_lo, e_hi, (hipStream_t)stream);
+  return enqueue_step(ctx, kind, mode, a, &ctx->sigma[(size_t)r * cfg.p], e_lo, e_hi, (hipStream_t)stream);
 }
 
 extern "C" int gg_sgd_step(gg_ctx* ctx, float* w, const float* g, float* m, void* stream) {
@@ -434,5 +508,5 @@ extern "C" int gg_sgd_step(gg_ctx* ctx, float* w, const float* g, float* m, void
   a.mu = ctx->cfg.momentum;
   a.tiles = 0;
   a.rng = gg_range{0, 0, INT64_MAX, 0};
-  return enqueue_step(ctx, KIND_SGD, MODE_SYNC, a, 0, ctx->cfg.n, (hipStream_t)stream);
+  return enqueue_step(ctx, KIND_SGD, MODE_SYNC, a, ctx->sigma.data(), 0, ctx->cfg.n, (hipStream_t)stream);
 }

@@ -36,7 +36,7 @@ struct gg_range {
 struct gg_tuning {
   int32_t threads;        // workgroup size
   int32_t chunks;         // access-type items per thread per tile: 1, 2, 4, 8
-  int32_t blocks_per_cu;  // 0: one tile per workgroup; >0: grid-stride with this many workgroups per CU
+  int32_t blocks_per_cu;  // 0: no cap; >0: at most this many resident workgroups per CU (LDS reservation)
   int32_t nontemporal;    // 1: streaming (nt) loads and stores
 };
 
@@ -96,7 +96,8 @@ inline bool gg_aligned(const void* ptr, uintptr_t a) { return ((uintptr_t)ptr % 
 struct gg_grid {
   dim3 grid;
   dim3 block;
-  int64_t tiles;  // tiles per row
+  int64_t tiles;       // tiles per row
+  uint32_t lds_bytes;  // dynamic LDS reserved only to cap the workgroups resident on a CU
 };
 gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t rows);
 

@@ -97,7 +97,8 @@ def test_dissemination_data_path(mode, p, n, stride):
 
 @pytest.mark.parametrize("tune", [
     {gg.TUNE_THREADS: 64, gg.TUNE_CHUNKS: 1}, {gg.TUNE_THREADS: 128, gg.TUNE_CHUNKS: 4},
-    {gg.TUNE_THREADS: 256, gg.TUNE_CHUNKS: 8}, {gg.TUNE_BLOCKS_PER_CU: 2}, {gg.TUNE_BLOCKS_PER_CU: 8, gg.TUNE_CHUNKS: 4},
+    {gg.TUNE_THREADS: 256, gg.TUNE_CHUNKS: 8}, {gg.TUNE_BLOCKS_PER_CU: 0, gg.TUNE_CHUNKS: 2}, {gg.TUNE_BLOCKS_PER_CU: 3},
+    {gg.TUNE_BLOCKS_PER_CU: 8, gg.TUNE_CHUNKS: 4},
     {gg.TUNE_NONTEMPORAL: 0},
 ])
 def test_launch_shapes_never_change_results(tune):
