@@ -1,0 +1,133 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py
+times (default tuning, rank stride rounded up to 1024 elements).
+
+The step is elementwise in the parameter index, so the oracle restricted to a
+set of columns is exactly the restriction of the full result: the oracle runs
+on sampled windows (first/last 4096, every 64 Mi-element boundary, random
+windows) of all p ranks, fed with the initial device buffers read back for
+those columns.  Inputs are generated on the GPU by the seeded generator."""
+import numpy as np
+import pytest
+import torch
+
+import gg_synth
+import paper_1803_05880_amd as gg
+from oracle import gossip as og
+from oracle import schedule as sc
+from parity_util import assert_close_fp32
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _columns(n, num_random):
+    cols = np.unique(np.concatenate([np.arange(lo, hi) for lo, hi in
+                                     gg_synth.sample_windows(n, num_random=num_random, width=1024, seed=1)]))
+    return cols
+
+
+def _take(t, cols_dev):
+    return t.index_select(1, cols_dev).cpu().numpy()
+
+
+def _bench_stride(n):
+    return (n + 1023) // 1024 * 1024
+
+
+@pytest.mark.parametrize("staleness", [0, 1])
+def test_config4_scale_out_shape_sampled_windows(staleness):
+    # p=64 x ResNet50-sized buffers; synchronous, and staleness 1 through a double buffer
+    p, n, seed = 64, gg_synth.RESNET50_PARAMS, 0
+    stride = _bench_stride(n)
+    W, G, M = gg_synth.make_state(p, n, stride, seed=seed, device=DEV)
+    cols = _columns(n, 48)
+    cd = torch.as_tensor(cols, device=DEV)
+    Wo, Go, Mo = _take(W, cd), _take(G, cd), _take(M, cd)
+    ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=seed, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM,
+                     staleness=staleness)
+    W2 = torch.empty_like(W) if staleness else None
+    bufs = [W, W2]
+    steps = 8                                            # L = 6: crosses into the first shuffled communicator
+    for t in range(steps):
+        if staleness:
+            ctx.gossip_step(t, bufs[t & 1], G, M, w_next=bufs[(t & 1) ^ 1])
+        else:
+            ctx.gossip_step(t, W, G, M)
+        c = sc.partners(p, seed, p, sc.HYPERCUBE, t)[1]
+        assert ctx.partner(t)[1].tolist() == c
+        og.gossip_step(Wo, Go, Mo, c, gg_synth.LR, gg_synth.MOMENTUM, W_stale=Wo.copy() if staleness else None)
+    torch.cuda.synchronize()
+    Wfinal = bufs[steps & 1] if staleness else W
+    dw = assert_close_fp32(_take(Wfinal, cd), Wo, "W")
+    dm = assert_close_fp32(_take(M, cd), Mo, "M")
+    assert dw == 0 and dm == 0
+    assert torch.count_nonzero(Wfinal[:, n:]) == 0       # padding untouched
+    # property that holds at any size: partners hold identical weights after a synchronous step
+    if not staleness:
+        c = ctx.partner(steps - 1)[1]
+        for j in (0, 17, 63):
+            assert torch.equal(W[j, :n], W[int(c[j]), :n])
+    ctx.close()
+
+
+def test_config5_full_method_step_sampled_windows_and_shuffle():
+    # p=128 x ResNet50-sized buffers + partner-swap shuffle of 1,281,167 ids
+    from oracle import shuffle as sh
+    p, n, seed = 128, gg_synth.RESNET50_PARAMS, 0
+    stride = _bench_stride(n)
+    W, G, M = gg_synth.make_state(p, n, stride, seed=seed, device=DEV)
+    cols = _columns(n, 16)
+    cd = torch.as_tensor(cols, device=DEV)
+    Wo, Go, Mo = _take(W, cd), _take(G, cd), _take(M, cd)
+    off = sh.block_offsets(gg_synth.IMAGENET1K_TRAIN, p)
+    idx = gg_synth.make_indices(gg_synth.IMAGENET1K_TRAIN, DEV)
+    idx_o = sh.initial_indices(gg_synth.IMAGENET1K_TRAIN)
+    ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=seed, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM)
+    for t in [0, 1, 6, 7, 8]:                            # L = 7: steps 7, 8 use a shuffled communicator
+        ctx.gossip_step(t, W, G, M)
+        ctx.shuffle(t, gg.SHUF_PARTNER_SWAP, idx, off)
+        c = sc.partners(p, seed, p, sc.HYPERCUBE, t)[1]
+        og.gossip_step(Wo, Go, Mo, c, gg_synth.LR, gg_synth.MOMENTUM)
+        sh.partner_swap_step(idx_o, off, c, seed, t)
+    torch.cuda.synchronize()
+    assert assert_close_fp32(_take(W, cd), Wo, "W") == 0
+    assert assert_close_fp32(_take(M, cd), Mo, "M") == 0
+    assert np.array_equal(idx.cpu().numpy(), idx_o)
+    ctx.close()
+
+
+def test_config3_segments_and_allreduce_comparator_sampled_windows():
+    # p=16 x ResNet50-sized buffers in 161 per-layer segments with per-layer gradient scales;
+    # the recursive-doubling all-reduce + SGD runs on a copy of the same buffers
+    p, n, seed = 16, gg_synth.RESNET50_PARAMS, 0
+    stride = _bench_stride(n)
+    seg, scales = gg_synth.segment_layout(n, 161, seed=seed)
+    assert seg[0] == 0 and seg[-1] == n and len(seg) == 162 and (np.diff(seg) >= 1).all()
+    W, G, M = gg_synth.make_state(p, n, stride, seed=seed, device=DEV, seg_offsets=seg, seg_scales=scales)
+    cols = _columns(n, 64)
+    cd = torch.as_tensor(cols, device=DEV)
+    Wo, Go, Mo = _take(W, cd), _take(G, cd), _take(M, cd)
+    Wa, Ga, Ma = W.clone(), G.clone(), M.clone()
+    Wao, Gao, Mao = Wo.copy(), Go.copy(), Mo.copy()
+    ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=seed, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM)
+    for t in range(32):
+        ctx.gossip_step(t, W, G, M, seg_offsets=seg)
+        og.gossip_step(Wo, Go, Mo, sc.partners(p, seed, p, sc.HYPERCUBE, t)[1], gg_synth.LR, gg_synth.MOMENTUM)
+    for t in range(3):
+        Ga.copy_(G)
+        if t == 1:
+            ctx.allreduce_onepass(Ga, average=True)
+        else:
+            ctx.allreduce_baseline(Ga, average=True)
+        ctx.sgd_step(Wa, Ga, Ma)
+        Gao[...] = Go
+        og.allreduce_sgd_step(Wao, Gao, Mao, gg_synth.LR, gg_synth.MOMENTUM)
+    torch.cuda.synchronize()
+    assert assert_close_fp32(_take(W, cd), Wo, "W gossip") == 0
+    assert assert_close_fp32(_take(M, cd), Mo, "M gossip") == 0
+    assert assert_close_fp32(_take(Wa, cd), Wao, "W allreduce") == 0
+    assert assert_close_fp32(_take(Ma, cd), Mao, "M allreduce") == 0
+    assert assert_close_fp32(_take(Ga, cd), Gao, "G allreduce") == 0
+    # any size: after the all-reduce every rank holds the same gradient bits
+    assert torch.equal(Ga[0, :n], Ga[p - 1, :n])
+    ctx.close()
