@@ -189,14 +189,14 @@ extern "C" int gg_allreduce_baseline(gg_ctx* ctx, float* g, int32_t average, voi
     a.scale = 1.0f / (float)p;                        // rounding as scaling afterwards
     if (sp.body.count > 0) {
       a.rng = sp.body;
-      gg_grid gd = gg_make_grid(ctx, a.rng.count, ctx->tune.chunks, p / 2);
+      gg_grid gd = gg_make_grid(ctx, a.rng.count, ctx->tune.chunks, p / 2, 2);
       a.tiles = gd.tiles;
       launch_round<v4f>(ctx->tune.chunks, nt, gd, (hipStream_t)stream, a);
       GG_HIP_TRY(hipGetLastError());
     }
     if (sp.edge.count > 0) {
       a.rng = sp.edge;
-      gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, p / 2);
+      gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, p / 2, 2);
       a.tiles = gd.tiles;
       launch_round<float>(1, nt, gd, (hipStream_t)stream, a);
       GG_HIP_TRY(hipGetLastError());
@@ -219,14 +219,14 @@ extern "C" int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void
   a.scale = 1.0f / (float)ctx->cfg.p;
   if (sp.body.count > 0) {
     a.rng = sp.body;
-    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1);
+    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1, 12);
     a.tiles = gd.tiles;
     launch_onepass<v4f>(ctx->L, gd, (hipStream_t)stream, a);
     GG_HIP_TRY(hipGetLastError());
   }
   if (sp.edge.count > 0) {
     a.rng = sp.edge;
-    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1);
+    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1, 12);
     a.tiles = gd.tiles;
     launch_onepass<float>(ctx->L, gd, (hipStream_t)stream, a);
     GG_HIP_TRY(hipGetLastError());

@@ -50,7 +50,7 @@ int gg_check_ctx_device(const gg_ctx* ctx) {
   return dev == ctx->device ? GG_OK : GG_ERR_ARG;
 }
 
-gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t rows) {
+gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t rows, int32_t loads) {
   gg_grid out;
   const int64_t per_tile = (int64_t)ctx->tune.threads * chunks;
   out.tiles = (items + per_tile - 1) / per_tile;
@@ -65,7 +65,12 @@ gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t r
   // touched at once and cost row-buffer hits.
   out.lds_bytes = 0;
   if (ctx->tune.blocks_per_cu > 0) {
-    uint32_t b = (uint32_t)(160u * 1024u / (uint32_t)ctx->tune.blocks_per_cu) & ~255u;
+    // the cap is stated for 6 loads per thread and 64 threads; scale to this launch
+    int64_t cap = ((int64_t)ctx->tune.blocks_per_cu * 6 * 64 + (int64_t)loads * chunks * ctx->tune.threads / 2) /
+                  ((int64_t)loads * chunks * ctx->tune.threads);
+    if (cap < 2) cap = 2;
+    if (cap > 64) cap = 64;
+    uint32_t b = (uint32_t)(160u * 1024u / (uint32_t)cap) & ~255u;
     if (b > 64u * 1024u - 4096u) b = 64u * 1024u - 4096u;  // stay below the default dynamic-LDS limit
     out.lds_bytes = b;
   }

@@ -99,6 +99,9 @@ struct gg_grid {
   int64_t tiles;       // tiles per row
   uint32_t lds_bytes;  // dynamic LDS reserved only to cap the workgroups resident on a CU
 };
-gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t rows);
+// `loads` = 16-byte loads one thread keeps in flight; the occupancy cap is stated for the
+// pair kernel (6 loads per thread) and scaled so that every kernel keeps about the same
+// number of bytes in flight per CU.
+gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t rows, int32_t loads);
 
 #endif  // GG_INTERNAL_H_
