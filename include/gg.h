@@ -149,6 +149,14 @@ int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
  * device, 16-byte aligned, nbytes a multiple of 16. */
 int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream);
 
+/* Measurement aid: an arithmetic-only kernel (no memory traffic) that stands in
+ * for the forward/backward computation when the overlap of the layer-wise
+ * exchange with computation (Sec. 5, Sec. 5.1) is measured.  Runs `blocks`
+ * workgroups of 256 threads, each thread a dependent chain of `iters`
+ * multiply-adds.  sink: device float[1], written only if the chain ends on an
+ * impossible value (keeps the loop alive).  1 <= blocks <= 65536, iters >= 0. */
+int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream);
+
 /* Launch-shape knobs for bandwidth sweeps (never change results).  key:
  *   0 = threads per workgroup (64, 128 or 256; default 64),
  *   1 = 16-byte chunks per thread per tile (1, 2, 4, 8; default 1),

@@ -110,3 +110,14 @@ def allreduce_sgd_step(W, G, M, lr, mu):
     overwritten with the averaged gradient."""
     allreduce_recursive_doubling(G, average=True)
     sgd_step(W, G, M, lr, mu)
+
+
+def allreduce_every_log_p_block(W, G, M, lr, mu):
+    """The alternative of Sec. 7.5: every rank runs log2(p) local momentum-SGD
+    steps on its own, then the models are combined by one all-reduce (average of
+    the weights).  Momentum stays local.  Advances log2(p) steps in place."""
+    p = W.shape[0]
+    L = p.bit_length() - 1
+    for _ in range(L):
+        sgd_step(W, G, M, lr, mu)
+    allreduce_recursive_doubling(W, average=True)

@@ -66,12 +66,13 @@ def lib():
         L.gg_allreduce_onepass.argtypes = [vp, vp, i32, vp]
         L.gg_shuffle.argtypes = [vp, i64, i32, vp, vp, i32, vp]
         L.gg_copy_probe.argtypes = [vp, vp, i64, vp]
+        L.gg_busy_probe.argtypes = [i64, i32, vp, vp]
         L.gg_set_tuning.argtypes = [vp, i32, i32]
         L.gg_strerror.argtypes = [ctypes.c_int]
         L.gg_strerror.restype = ctypes.c_char_p
         for name in ("gg_init", "gg_destroy", "gg_partner", "gg_gossip_step", "gg_sgd_step",
                      "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_copy_probe",
-                     "gg_set_tuning"):
+                     "gg_busy_probe", "gg_set_tuning"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -176,3 +177,9 @@ def copy_probe(dst, src, stream=None):
         raise ValueError("size mismatch")
     _check(lib().gg_copy_probe(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), nbytes,
                                _stream_ptr(stream)), "gg_copy_probe")
+
+
+def busy_probe(iters, blocks, sink, stream=None):
+    """gg_busy_probe: arithmetic-only stand-in for forward/backward computation."""
+    _check(lib().gg_busy_probe(int(iters), int(blocks), _dev_ptr(sink, torch.float32, "sink"), _stream_ptr(stream)),
+           "gg_busy_probe")

@@ -111,6 +111,12 @@ __global__ void __launch_bounds__(256) copy_kernel(v4f* dst, const v4f* src, int
     __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+__global__ void __launch_bounds__(256) busy_kernel(int64_t iters, float* sink) {
+  float x = 1.0f + (float)threadIdx.x * 1e-7f, y = 0.999999f;
+  for (int64_t i = 0; i < iters; ++i) x = x * y + 1e-9f;
+  if (x == -1.0f) *sink = x;  // never true: the chain stays positive
+}
+
 template <typename V>
 void launch_round(int U, bool nt, const gg_grid& gd, hipStream_t s, const ar_args& a) {
 #define GG_CASE(UU)                                                                            \
@@ -245,6 +251,14 @@ extern "C" int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* s
   if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(64), 0, (hipStream_t)stream, (v4f*)dst,
                      (const v4f*)src, count);
+  GG_HIP_TRY(hipGetLastError());
+  return GG_OK;
+}
+
+extern "C" int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream) {
+  if (!sink || iters < 0 || blocks < 1 || blocks > 65536) return GG_ERR_ARG;
+  if (!gg_aligned(sink, 4)) return GG_ERR_ALIGN;
+  hipLaunchKernelGGL(busy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, iters, sink);
   GG_HIP_TRY(hipGetLastError());
   return GG_OK;
 }

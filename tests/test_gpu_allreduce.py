@@ -68,3 +68,24 @@ def test_allreduce_needs_power_of_two():
         ctx.allreduce_baseline(g)
     assert e.value.code == gg.binding.GG_ERR_NOT_POW2
     ctx.close()
+
+
+def test_allreduce_every_log_p_steps_block_matches_oracle():
+    # Sec. 7.5: log2(p) local steps, then one all-reduce of the models
+    p, n, stride = 16, 250_003, 250_004
+    W, G, M = host_state(p, n, stride, seed=14)
+    ctx = gg.Context(p=p, n=n, rank_stride=stride, lr=0.1, momentum=0.9)
+    w, g, m = W.to(DEV), G.to(DEV), M.to(DEV)
+    Wo, Go, Mo = (a[:, :n].numpy().copy() for a in (W, G, M))
+    for block in range(2):
+        for _ in range(4):
+            ctx.sgd_step(w, g, m)
+        if block:
+            ctx.allreduce_onepass(w, average=True)
+        else:
+            ctx.allreduce_baseline(w, average=True)
+        og.allreduce_every_log_p_block(Wo, Go, Mo, 0.1, 0.9)
+    torch.cuda.synchronize()
+    assert assert_close_fp32(w.cpu()[:, :n].numpy(), Wo, "W") == 0
+    assert assert_close_fp32(m.cpu()[:, :n].numpy(), Mo, "M") == 0
+    ctx.close()

@@ -267,3 +267,24 @@ def test_fp32_oracle_tracks_float64_oracle():
         og.gossip_step(W64, G64, M64, c, np.float32(0.1), np.float32(0.9))
     scale = np.abs(W64).max()
     assert np.abs(W - W64).max() <= 9 * 4 * 2.0**-24 * scale
+
+
+def test_allreduce_every_log_p_block_is_local_steps_then_model_mean():
+    # Sec. 7.5: O(1) amortised communication by combining the models every log p steps
+    p, n = 8, 200
+    W, G, M = _state(p, n, 16, np.float64)
+    W0, M0 = W.copy(), M.copy()
+    og.allreduce_every_log_p_block(W, G, M, 0.1, 0.9)
+    # closed form per rank after 3 local steps with constant g: w3 = w0 - sum_t v_t, v_t = mu^t m0 + lr g (1-mu^t)/(1-mu)
+    vs = [0.9**t * M0 + 0.1 * G * (1 - 0.9**t) / (1 - 0.9) for t in (1, 2, 3)]
+    local = W0 - sum(vs)
+    np.testing.assert_allclose(M, vs[-1], rtol=1e-12, atol=1e-18)
+    for j in range(p):
+        np.testing.assert_allclose(W[j], local.mean(axis=0), rtol=1e-12, atol=1e-16)
+    # identical ranks: the block equals three plain SGD steps bit for bit
+    W1, G1, M1 = _state(1, n, 17)
+    Wp, Gp, Mp = (np.repeat(a, p, axis=0) for a in (W1, G1, M1))
+    og.allreduce_every_log_p_block(Wp, Gp, Mp, 0.1, 0.9)
+    for _ in range(3):
+        og.sgd_step(W1, G1, M1, 0.1, 0.9)
+    assert all(np.array_equal(Wp[j], W1[0]) for j in range(p))
