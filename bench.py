@@ -287,6 +287,26 @@ def main():
         _, pr = time_loop(torch, shuf, reps, 2)
         extras["shuffle_ms"] = round(sum(event_ms(pr)) / len(pr), 4)
 
+        # ring rotation of the sample payload: 64 resident samples per rank, batch 32,
+        # 256x256x3-byte samples (Table 5); bytes moved = read + write of p*batch samples
+        sample_bytes, resident, batch = 196_608, 64, 32
+        pay = torch.zeros((p * resident, sample_bytes // 4), dtype=torch.int32, device=dev)
+        pay.random_(0, 2**31 - 1)
+        poff = gg_synth.block_offsets(p * resident, p)
+
+        def payload(t, pairs):
+            a, b = ev(), ev()
+            a.record(stream)
+            ctx.shuffle_payload(t, pay, poff, batch)
+            b.record(stream)
+            if pairs is not None:
+                pairs.append((a, b))
+        _, pr = time_loop(torch, payload, reps, 2)
+        pay_ms = sum(event_ms(pr)) / len(pr)
+        extras["payload_ring_shuffle"] = {"ms": round(pay_ms, 4), "batch": batch, "sample_bytes": sample_bytes,
+                                          "GBps": round(2.0 * p * batch * sample_bytes / (pay_ms * 1e-3) / 1e9, 1)}
+        del pay
+
         # plain copy kernel on a W-sized buffer (read + write = 2 x bytes)
         scratch = torch.empty_like(W)
 

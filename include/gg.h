@@ -144,6 +144,17 @@ int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void* stream);
 int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
                const int64_t* rank_offsets, int32_t batch, void* stream);
 
+/* The ring rotation of gg_shuffle(GG_SHUF_RING) applied to the samples themselves
+ * (Sec. 4.5.2: a rank sends the batch it has just used to its ring neighbour;
+ * Table 5 gives the sample sizes): slot s of rank j is the sample_bytes bytes at
+ * payload + (rank_offsets[j] + s) * sample_bytes, and the slots move exactly as the
+ * indices do, so an index array and a payload array rotated with the same
+ * (step, batch) stay in correspondence.  In place, every byte read once and written
+ * once.  payload: device, 4-byte aligned (16-byte aligned with sample_bytes % 16 == 0
+ * for the vector path); sample_bytes > 0, multiple of 4; 0 <= batch <= min n_j. */
+int gg_shuffle_payload(gg_ctx* ctx, int64_t step, void* payload, int64_t sample_bytes,
+                       const int64_t* rank_offsets, int32_t batch, void* stream);
+
 /* Measurement aid: plain device-to-device copy kernel (16-byte loads/stores) used
  * to calibrate achievable memory bandwidth next to the gossip kernel.  dst, src:
  * device, 16-byte aligned, nbytes a multiple of 16. */

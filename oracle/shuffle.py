@@ -91,3 +91,12 @@ def ring_current_batch(idx, off, batch, t, j):
     n_j = off[j + 1] - off[j]
     h = (t * batch) % n_j
     return [int(idx[off[j] + (h + r) % n_j]) for r in range(batch)]
+
+
+def ring_payload_step(payload, off, batch, t):
+    """The ring step applied to the samples themselves: `payload` is [n_total][...],
+    row s holds the sample resident in slot s.  Rows move exactly as the indices
+    do under ring_step.  In place."""
+    src = np.arange(payload.shape[0], dtype=np.int32)
+    ring_step(src, off, batch, t)            # src[d] = slot whose content lands in slot d
+    payload[...] = payload[src]

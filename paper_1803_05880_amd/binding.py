@@ -65,13 +65,14 @@ def lib():
         L.gg_allreduce_baseline.argtypes = [vp, vp, i32, vp]
         L.gg_allreduce_onepass.argtypes = [vp, vp, i32, vp]
         L.gg_shuffle.argtypes = [vp, i64, i32, vp, vp, i32, vp]
+        L.gg_shuffle_payload.argtypes = [vp, i64, vp, i64, vp, i32, vp]
         L.gg_copy_probe.argtypes = [vp, vp, i64, vp]
         L.gg_busy_probe.argtypes = [i64, i32, vp, vp]
         L.gg_set_tuning.argtypes = [vp, i32, i32]
         L.gg_strerror.argtypes = [ctypes.c_int]
         L.gg_strerror.restype = ctypes.c_char_p
         for name in ("gg_init", "gg_destroy", "gg_partner", "gg_gossip_step", "gg_sgd_step",
-                     "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_copy_probe",
+                     "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_shuffle_payload", "gg_copy_probe",
                      "gg_busy_probe", "gg_set_tuning"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -165,6 +166,16 @@ class Context:
             raise ValueError("rank_offsets must have p+1 entries")
         _check(lib().gg_shuffle(self._h, step, mode, _dev_ptr(idx, torch.int32, "idx"),
                                 off.ctypes.data_as(ctypes.c_void_p), batch, _stream_ptr(stream)), "gg_shuffle")
+
+    def shuffle_payload(self, step, payload, rank_offsets, batch, stream=None):
+        """gg_shuffle_payload: payload is a 2-D CUDA tensor [n_total][sample elements]."""
+        off = np.ascontiguousarray(rank_offsets, dtype=np.int64)
+        if off.shape != (self.p + 1,) or payload.dim() != 2 or not payload.is_cuda or not payload.is_contiguous():
+            raise ValueError("payload must be a contiguous CUDA tensor [n_total][sample] and rank_offsets p+1 long")
+        sample_bytes = payload.shape[1] * payload.element_size()
+        _check(lib().gg_shuffle_payload(self._h, step, ctypes.c_void_p(payload.data_ptr()), sample_bytes,
+                                        off.ctypes.data_as(ctypes.c_void_p), batch, _stream_ptr(stream)),
+               "gg_shuffle_payload")
 
     def set_tuning(self, key, value):
         _check(lib().gg_set_tuning(self._h, key, value), "gg_set_tuning")

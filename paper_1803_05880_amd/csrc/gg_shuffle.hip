@@ -125,8 +125,32 @@ __global__ void __launch_bounds__(256) ring_scatter_kernel(ring_args a) {
     a.idx[ring_slot(a, j, r)] = a.stage[(int64_t)src * a.batch + r];
 }
 
+// Ring rotation of the sample payload itself: the same slot movement as the index
+// ring, on rows of `words` W-sized words.  One thread owns word x of batch entry r
+// for ALL ranks and walks the ring once (hold rank p-1's word, then for j = 0..p-1
+// swap the held word into rank j's slot), so every byte is read once and written
+// once, in place, without staging.
+template <typename Wd>
+__global__ void __launch_bounds__(256) ring_payload_kernel(ring_args a, Wd* payload, int64_t words) {
+  const int64_t total = (int64_t)a.batch * words;
+  for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+    const int32_t r = (int32_t)(t / words);
+    const int64_t x = t - (int64_t)r * words;
+    Wd held = __builtin_nontemporal_load(payload + ring_slot(a, a.p - 1, r) * words + x);
+    Wd cur = __builtin_nontemporal_load(payload + ring_slot(a, 0, r) * words + x);
+    for (int32_t j = 0; j < a.p; ++j) {
+      Wd* dst = payload + ring_slot(a, j, r) * words + x;
+      Wd nxt = cur;
+      if (j + 1 < a.p) nxt = __builtin_nontemporal_load(payload + ring_slot(a, j + 1, r) * words + x);
+      __builtin_nontemporal_store(held, dst);
+      held = cur;
+      cur = nxt;
+    }
+  }
+}
+
 // Make the device copy of rank_offsets current and the scratch large enough.
-int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s) {
+int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s, bool need_scratch) {
   const int32_t p = ctx->cfg.p;
   const int64_t n_total = off[p];
   if (!ctx->d_offsets) {
@@ -146,7 +170,7 @@ int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s) {
                               hipMemcpyHostToDevice, s));
     ctx->offsets_cached.assign(off, off + p + 1);
   }
-  if (n_total > ctx->scratch_cap) {
+  if (need_scratch && n_total > ctx->scratch_cap) {
     GG_HIP_TRY(hipDeviceSynchronize());
     if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
     ctx->d_scratch = nullptr;
@@ -185,7 +209,7 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
   if (rc != GG_OK) return rc;
   if (rank_offsets[p] == 0) return GG_OK;
   hipStream_t s = (hipStream_t)stream;
-  rc = prepare(ctx, rank_offsets, s);
+  rc = prepare(ctx, rank_offsets, s, true);
   if (rc != GG_OK) return rc;
 
   if (mode == GG_SHUF_PARTNER_SWAP) {
@@ -218,5 +242,44 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
     hipLaunchKernelGGL(ring_scatter_kernel, dim3(bx, p), dim3(256), 0, s, a);
     GG_HIP_TRY(hipGetLastError());
   }
+  return GG_OK;
+}
+
+extern "C" int gg_shuffle_payload(gg_ctx* ctx, int64_t step, void* payload, int64_t sample_bytes,
+                                  const int64_t* rank_offsets, int32_t batch, void* stream) {
+  if (!ctx || !payload || !rank_offsets || step < 0 || sample_bytes <= 0 || sample_bytes % 4) return GG_ERR_ARG;
+  if (!gg_aligned(payload, 4)) return GG_ERR_ALIGN;
+  const int32_t p = ctx->cfg.p;
+  if (rank_offsets[0] != 0) return GG_ERR_ARG;
+  int64_t min_n = INT64_MAX;
+  for (int32_t j = 0; j < p; ++j) {
+    const int64_t n_j = rank_offsets[j + 1] - rank_offsets[j];
+    if (n_j < 0 || n_j > 0x7fffffffLL) return GG_ERR_ARG;
+    if (n_j < min_n) min_n = n_j;
+  }
+  if (batch < 0 || batch > min_n) return GG_ERR_ARG;
+  if (rank_offsets[p] > (int64_t(1) << 34) || sample_bytes > (int64_t(1) << 30)) return GG_ERR_ARG;
+  int rc = gg_check_ctx_device(ctx);
+  if (rc != GG_OK) return rc;
+  if (batch == 0) return GG_OK;
+  hipStream_t s = (hipStream_t)stream;
+  rc = prepare(ctx, rank_offsets, s, false);
+  if (rc != GG_OK) return rc;
+  ring_args a;
+  a.idx = nullptr;
+  a.stage = nullptr;
+  a.off = ctx->d_offsets;
+  a.step = step;
+  a.batch = batch;
+  a.p = p;
+  const bool vec = gg_aligned(payload, 16) && sample_bytes % 16 == 0;
+  const int64_t words = vec ? sample_bytes / 16 : sample_bytes / 4;
+  int64_t blocks = ((int64_t)batch * words + 255) / 256;
+  if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
+  if (vec)
+    hipLaunchKernelGGL(ring_payload_kernel<v4f>, dim3((unsigned)blocks), dim3(256), 0, s, a, (v4f*)payload, words);
+  else
+    hipLaunchKernelGGL(ring_payload_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, a, (float*)payload, words);
+  GG_HIP_TRY(hipGetLastError());
   return GG_OK;
 }

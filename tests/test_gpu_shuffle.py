@@ -89,3 +89,38 @@ def test_shuffle_argument_errors():
     torch.cuda.synchronize()
     assert np.array_equal(idx.cpu().numpy(), np.arange(100))
     ctx.close()
+
+
+@pytest.mark.parametrize("p,n_total,batch,sample_words", [(3, 12, 2, 4), (4, 64, 4, 12), (8, 1000, 17, 5),
+                                                          (16, 4096, 32, 3072), (128, 128 * 40, 32, 1024)])
+def test_ring_payload_bit_exact_and_glued_to_indices(p, n_total, batch, sample_words):
+    off = sh.block_offsets(n_total, p)
+    rng = np.random.default_rng(5)
+    pay_o = rng.integers(-2**31, 2**31 - 1, size=(n_total, sample_words), dtype=np.int64).astype(np.int32)
+    pay_o[:, 0] = np.arange(n_total)                        # tag: word 0 is the sample id
+    pay_g = torch.from_numpy(pay_o.copy()).to(DEV)
+    idx_g = gg_synth.make_indices(n_total, DEV)
+    ctx = gg.Context(p=p, n=4, topology=gg.TOPO_DISSEMINATION)
+    for t in [0, 1, 2, 3, 11, 10**6 + 3]:
+        sh.ring_payload_step(pay_o, off, batch, t)
+        ctx.shuffle_payload(t, pay_g, off, batch)
+        ctx.shuffle(t, gg.SHUF_RING, idx_g, off, batch=batch)
+        got = pay_g.cpu().numpy()
+        assert np.array_equal(got, pay_o), "step %d" % t
+        assert np.array_equal(got[:, 0], idx_g.cpu().numpy())   # payload rows follow their indices
+    ctx.close()
+
+
+def test_ring_payload_unaligned_rows_take_the_word_path():
+    p, n_total, batch = 4, 40, 3
+    off = sh.block_offsets(n_total, p)
+    pay_o = np.arange(n_total * 7, dtype=np.int32).reshape(n_total, 7)      # 28-byte rows
+    pay_g = torch.from_numpy(pay_o.copy()).to(DEV)
+    ctx = gg.Context(p=p, n=4)
+    for t in range(5):
+        sh.ring_payload_step(pay_o, off, batch, t)
+        ctx.shuffle_payload(t, pay_g, off, batch)
+    assert np.array_equal(pay_g.cpu().numpy(), pay_o)
+    with pytest.raises(gg.GGError):
+        ctx.shuffle_payload(0, pay_g, off, 11)
+    ctx.close()

@@ -136,3 +136,15 @@ def test_partner_swap_rejects_non_involution():
         sh.partner_swap_step(sh.initial_indices(30), off, [1, 2, 0], 0, 0)
     with pytest.raises(ValueError):
         sh.partner_swap_step(sh.initial_indices(20), sh.block_offsets(20, 2), [0, 1], 0, 0)
+
+
+def test_ring_payload_follows_the_indices():
+    # a payload row tagged with its sample id must stay glued to that id
+    p, n, b = 4, 37, 3
+    off = sh.block_offsets(n, p)
+    idx = sh.initial_indices(n)
+    payload = np.stack([np.arange(n) * 10, np.arange(n) * 10 + 1, np.arange(n) * 10 + 2], axis=1).astype(np.int32)
+    for t in range(25):
+        sh.ring_step(idx, off, b, t)
+        sh.ring_payload_step(payload, off, b, t)
+        assert np.array_equal(payload[:, 0], idx * 10) and np.array_equal(payload[:, 2], idx * 10 + 2)
