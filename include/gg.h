@@ -57,7 +57,8 @@ enum { GG_SHUF_PARTNER_SWAP = 0, GG_SHUF_RING = 1 };
 
 #define GG_MAX_RANKS 1024
 
-typedef struct gg_ctx gg_ctx; /* opaque; owns only its schedule tables and shuffle scratch */
+typedef struct gg_ctx gg_ctx; /* opaque; owns only its schedule tables and scratch (shuffle lists,
+                                 dissemination carry column) */
 
 typedef struct {
   int32_t p;           /* virtual ranks, 2 .. GG_MAX_RANKS; power of two for hypercube     */
@@ -174,7 +175,9 @@ int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream);
  *   2 = cap on resident workgroups per CU, enforced by reserving LDS
  *       (0 = no cap, 3..64; default 10: few waves in flight keep the DRAM
  *       row-buffer working set small, which is what the streaming kernels want),
- *   3 = non-temporal loads/stores (0/1; default 1). */
+ *   3 = non-temporal loads/stores (0/1; default 1),
+ *   4 = dissemination: hops per launch when a long partner cycle is walked in
+ *       groups (0 = always one launch, 2..1024; default 8). */
 int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value);
 
 /* Static, never NULL. */

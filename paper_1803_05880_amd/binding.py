@@ -21,7 +21,7 @@ TOPO_HYPERCUBE, TOPO_DISSEMINATION = 0, 1
 AVG_MODEL, AVG_GRAD, AVG_NONE = 0, 1, 2
 SHUF_PARTNER_SWAP, SHUF_RING = 0, 1
 MAX_RANKS = 1024
-TUNE_THREADS, TUNE_CHUNKS, TUNE_BLOCKS_PER_CU, TUNE_NONTEMPORAL = 0, 1, 2, 3
+TUNE_THREADS, TUNE_CHUNKS, TUNE_BLOCKS_PER_CU, TUNE_NONTEMPORAL, TUNE_HOP_GROUP = 0, 1, 2, 3, 4
 
 
 class GGConfig(ctypes.Structure):

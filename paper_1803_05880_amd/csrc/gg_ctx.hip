@@ -101,7 +101,9 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
   ctx->scratch_cap = 0;
   ctx->d_offsets = nullptr;
   ctx->h_offsets_pinned = nullptr;
-  ctx->tune = gg_tuning{64, 1, 10, 1};
+  ctx->tune = gg_tuning{64, 1, 10, 1, 8};
+  ctx->d_carry = nullptr;
+  ctx->carry_cap = 0;
 
   const size_t entries = (size_t)ctx->R * (size_t)cfg->p;
   try {
@@ -161,6 +163,7 @@ extern "C" int gg_destroy(gg_ctx* ctx) {
   if (hipDeviceSynchronize() != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->d_sigma && hipFree(ctx->d_sigma) != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->d_scratch && hipFree(ctx->d_scratch) != hipSuccess) rc = GG_ERR_HIP;
+  if (ctx->d_carry && hipFree(ctx->d_carry) != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->d_offsets && hipFree(ctx->d_offsets) != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->h_offsets_pinned && hipHostFree(ctx->h_offsets_pinned) != hipSuccess) rc = GG_ERR_HIP;
   if (rc != GG_OK) (void)hipGetLastError();
@@ -208,6 +211,10 @@ extern "C" int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value) {
     case 3:
       if (value != 0 && value != 1) return GG_ERR_ARG;
       ctx->tune.nontemporal = value;
+      return GG_OK;
+    case 4:
+      if (value < 0 || value == 1 || value > GG_MAX_RANKS) return GG_ERR_ARG;
+      ctx->tune.hop_group = value;
       return GG_OK;
     default:
       return GG_ERR_ARG;

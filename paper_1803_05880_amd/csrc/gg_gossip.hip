@@ -202,13 +202,26 @@ __global__ void __launch_bounds__(64) gossip_pair_lean_kernel(step_args a, pair_
 // thread walks its cycle for one chunk and carries the previous rank's
 // contribution in registers, so each rank's w, g, m are read once and written
 // once, in place.  The communicator row sits in LDS (read at every hop).
-template <typename V, int MODE, int U, bool NT>
-__global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, int32_t cycle_len) {
+// A long cycle keeps 5 address streams open per rank on it, and bandwidth falls
+// with the number of streams touched at once.  SPLIT cuts the walk into groups
+// of consecutive hops, one launch per group, LAST group first: a group's
+// carry-in is recomputed from the (still untouched) rank before it, and the
+// contribution of the cycle's last rank to its first is parked in a carry column
+// by the first launch and picked up by the last one.
+struct cycle_args {
+  int32_t cycle_len;
+  int32_t t_begin, t_end;  // hops handled by this launch (whole cycle when not split)
+  float* carry;            // [cycles][stride] parking column, split launches only
+};
+
+template <typename V, int MODE, int U, bool NT, bool SPLIT>
+__global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_args ca) {
   __shared__ uint16_t s_sigma[GG_MAX_RANKS];
   for (int32_t i = threadIdx.x; i < a.p; i += blockDim.x) s_sigma[i] = a.sigma[i];
   __syncthreads();
   const int32_t v0 = blockIdx.y;
-  const int64_t rank0 = s_sigma[v0];
+  // world rank at hop t of this cycle: virtual rank (v0 + t*shift) mod p
+  auto rank_at = [&](int32_t t) -> int64_t { return s_sigma[(v0 + t * a.shift) % a.p]; };
   const int64_t per_tile = (int64_t)blockDim.x * U;
   for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
     int64_t idx[U];
@@ -231,56 +244,71 @@ __global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, int32_t 
           m[u] = ld<NT>(pm + idx[u]);
         }
     };
-    auto store_m = [&](int64_t rank, const V* v) {
-      V* pm = reinterpret_cast<V*>(a.m + rank * a.stride);
+    auto load_one = [&](const float* base, int64_t row, V* out) {
+      const V* ptr = reinterpret_cast<const V*>(base + row * a.stride);
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (on[u]) st<NT>(pm + idx[u], v[u]);
+        if (on[u]) out[u] = ld<NT>(ptr + idx[u]);
     };
-    auto store_w = [&](int64_t rank, const V* out) {
-      V* pn = reinterpret_cast<V*>(a.wn + rank * a.stride);
+    auto store_one = [&](float* base, int64_t row, const V* val) {
+      V* ptr = reinterpret_cast<V*>(base + row * a.stride);
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (on[u]) st<NT>(pn + idx[u], out[u]);
+        if (on[u]) st<NT>(ptr + idx[u], val[u]);
     };
 
-    // first rank of the cycle: its new weights need the LAST rank's contribution
     V fw[U], fg[U], fm[U], fT[U];
     V carry[U];  // what the previous rank on the walk contributes to the next one
-    load(rank0, fw, fg, fm);
-    if (MODE == MODE_GRAD) {
+    int32_t t_first;
+    const int64_t rank0 = rank_at(0);
+    if (!SPLIT) {
+      // first rank of the cycle: its new weights need the LAST rank's contribution
+      load(rank0, fw, fg, fm);
+      if (MODE == MODE_GRAD) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) carry[u] = fg[u];
-    } else {
-      V v[U];
+        for (int u = 0; u < U; ++u) carry[u] = fg[u];
+      } else {
+        V v[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        fT[u] = local_update(fw[u], fg[u], fm[u], a.lr, a.mu, v[u]);
-        carry[u] = (MODE == MODE_SYNC) ? fT[u] : fw[u];
+        for (int u = 0; u < U; ++u) {
+          fT[u] = local_update(fw[u], fg[u], fm[u], a.lr, a.mu, v[u]);
+          carry[u] = (MODE == MODE_SYNC) ? fT[u] : fw[u];
+        }
+        store_one(a.m, rank0, v);
       }
-      store_m(rank0, v);
+      t_first = 1;
+    } else {
+      t_first = ca.t_begin;
+      const int64_t prev = rank_at(ca.t_begin == 0 ? ca.cycle_len - 1 : ca.t_begin - 1);
+      if (MODE == MODE_GRAD) {
+        load_one(a.g, prev, carry);  // gradients are never written: always the original
+      } else if (ca.t_begin == 0) {
+        load_one(ca.carry, v0, carry);  // parked by the launch that handled the last hops
+      } else if (MODE == MODE_STALE) {
+        load_one(a.w, prev, carry);  // rank `prev` belongs to a later launch: still untouched
+      } else {
+        V pw[U], pg[U], pm[U], v[U];
+        load(prev, pw, pg, pm);
+#pragma unroll
+        for (int u = 0; u < U; ++u) carry[u] = local_update(pw[u], pg[u], pm[u], a.lr, a.mu, v[u]);
+      }
     }
+
     // The walk keeps three ranks in flight: the one being finished and the next two.
     // Stores and loads retire through one in-order counter, so waiting for a rank's
     // loads also waits for every store issued before them; with two ranks of
     // look-ahead those are the stores of two hops ago, long since acknowledged.
-    auto next_v = [&](int32_t v) {
-      v += a.shift;
-      return v >= a.p ? v - a.p : v;
-    };
-    int32_t v1 = next_v(v0);
-    int32_t v2 = next_v(v1);
-    int64_t rank = s_sigma[v1];
-    int64_t rank_1 = s_sigma[v2];
+    const int32_t t_end = ca.t_end;
+    int64_t rank = rank_at(t_first);
+    int64_t rank_1 = rank_at(t_first + 1);
     V cw[U], cg[U], cm[U];
     V n1w[U], n1g[U], n1m[U];
-    if (cycle_len > 1) load(rank, cw, cg, cm);
-    if (cycle_len > 2) load(rank_1, n1w, n1g, n1m);
-    for (int32_t t = 1; t < cycle_len; ++t) {
-      const int32_t v3 = next_v(v2);
-      const int64_t rank_2 = s_sigma[v3];
+    if (t_first < t_end) load(rank, cw, cg, cm);
+    if (t_first + 1 < t_end) load(rank_1, n1w, n1g, n1m);
+    for (int32_t t = t_first; t < t_end; ++t) {
+      const int64_t rank_2 = rank_at(t + 2);
       V n2w[U], n2g[U], n2m[U];
-      if (t + 2 < cycle_len) load(rank_2, n2w, n2g, n2m);
+      if (t + 2 < t_end) load(rank_2, n2w, n2g, n2m);
       V v[U], out[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -294,8 +322,8 @@ __global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, int32_t 
           carry[u] = (MODE == MODE_SYNC) ? T : cw[u];
         }
       }
-      store_m(rank, v);
-      store_w(rank, out);
+      store_one(a.m, rank, v);
+      store_one(a.wn, rank, out);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         cw[u] = n1w[u];
@@ -305,25 +333,28 @@ __global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, int32_t 
         n1g[u] = n2g[u];
         n1m[u] = n2m[u];
       }
-      v2 = v3;
       rank = rank_1;
       rank_1 = rank_2;
     }
-    // close the cycle
-    V out[U];
-    if (MODE == MODE_GRAD) {
-      V v[U];
+    if (!SPLIT) {
+      // close the cycle
+      V out[U];
+      if (MODE == MODE_GRAD) {
+        V v[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const V gbar = (fg[u] + carry[u]) * 0.5f;
-        out[u] = local_update(fw[u], gbar, fm[u], a.lr, a.mu, v[u]);
+        for (int u = 0; u < U; ++u) {
+          const V gbar = (fg[u] + carry[u]) * 0.5f;
+          out[u] = local_update(fw[u], gbar, fm[u], a.lr, a.mu, v[u]);
+        }
+        store_one(a.m, rank0, v);
+      } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) out[u] = (fT[u] + carry[u]) * 0.5f;
       }
-      store_m(rank0, v);
-    } else {
-#pragma unroll
-      for (int u = 0; u < U; ++u) out[u] = (fT[u] + carry[u]) * 0.5f;
+      store_one(a.wn, rank0, out);
+    } else if (MODE != MODE_GRAD && t_end == ca.cycle_len) {
+      store_one(ca.carry, v0, carry);  // the last rank's contribution to the first
     }
-    store_w(rank0, out);
   }
 }
 
@@ -378,14 +409,14 @@ struct launch_ctx {
   gg_grid gd;
   hipStream_t s;
   const pair_table* pt;
-  int32_t cycle_len;
+  cycle_args ca;
+  bool split;
 };
 
 template <typename V, int MODE, int U, bool NT>
 void launch_one(int kind, const launch_ctx& lc, const step_args& a) {
   const gg_grid& gd = lc.gd;
   hipStream_t s = lc.s;
-  const int32_t cycle_len = lc.cycle_len;
   if (kind == KIND_PAIR) {
     if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles)
       hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, *lc.pt);
@@ -393,7 +424,12 @@ void launch_one(int kind, const launch_ctx& lc, const step_args& a) {
       hipLaunchKernelGGL((gossip_pair_kernel<V, MODE, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, *lc.pt);
   }
   else if (kind == KIND_CYCLE)
-    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, (U > 4 ? 4 : U), NT>), gd.grid, gd.block, gd.lds_bytes, s, a, cycle_len);
+    if (lc.split)
+      hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, (U > 2 ? 2 : U), NT, true>), gd.grid, gd.block, gd.lds_bytes, s,
+                         a, lc.ca);
+    else
+      hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, (U > 2 ? 2 : U), NT, false>), gd.grid, gd.block, gd.lds_bytes,
+                         s, a, lc.ca);
   else
     hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a);
 }
@@ -469,21 +505,51 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
     if (body_hi < body_lo) body_hi = body_lo = e_lo;
   }
   const bool nt = ctx->tune.nontemporal != 0;
-  if (body_hi > body_lo) {
-    const int U = kind == KIND_CYCLE ? (ctx->tune.chunks > 4 ? 4 : ctx->tune.chunks) : ctx->tune.chunks;
-    a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
-    launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, kind == KIND_SGD ? 3 : 6), s, &pt, cycle_len};
-    a.tiles = lc.gd.tiles;
-    launch_any<v4f>(kind, mode, U, nt, lc, a);
-    GG_HIP_TRY(hipGetLastError());
-  }
   const int64_t edge = (body_lo - e_lo) + (e_hi - body_hi);
-  if (edge > 0) {
-    a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
-    launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, kind == KIND_SGD ? 3 : 6), s, &pt, cycle_len};
-    a.tiles = lc.gd.tiles;
-    launch_any<float>(kind, mode, 1, nt, lc, a);
-    GG_HIP_TRY(hipGetLastError());
+  const int loads = kind == KIND_SGD ? 3 : 6;
+
+  // Long dissemination cycles are walked in groups of hops, last group first.
+  const int32_t hop_group = ctx->tune.hop_group;
+  bool split = kind == KIND_CYCLE && hop_group > 0 && cycle_len > hop_group + hop_group / 2;
+  if (split && mode != MODE_GRAD) {
+    const int64_t need = rows * a.stride;  // one parking column per cycle
+    if (need > (int64_t(1) << 31)) {
+      split = false;  // would need more than 8 GiB of scratch: walk whole cycles instead
+    } else if (need > ctx->carry_cap) {
+      GG_HIP_TRY(hipDeviceSynchronize());
+      if (ctx->d_carry) (void)hipFree(ctx->d_carry);
+      ctx->d_carry = nullptr;
+      ctx->carry_cap = 0;
+      if (hipMalloc((void**)&ctx->d_carry, (size_t)need * sizeof(float)) != hipSuccess) {
+        (void)hipGetLastError();
+        return GG_ERR_NOMEM;
+      }
+      ctx->carry_cap = need;
+    }
+  }
+  const int32_t groups = split ? (cycle_len + hop_group - 1) / hop_group : 1;
+  for (int32_t gi = groups - 1; gi >= 0; --gi) {
+    cycle_args ca;
+    ca.cycle_len = cycle_len;
+    ca.t_begin = split ? gi * hop_group : 0;
+    ca.t_end = split ? (ca.t_begin + hop_group < cycle_len ? ca.t_begin + hop_group : cycle_len) : cycle_len;
+    ca.carry = ctx->d_carry;
+    if (body_hi > body_lo) {
+      int U = ctx->tune.chunks;
+      if (kind == KIND_CYCLE && U > 2) U = 2;
+      a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
+      launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, loads), s, &pt, ca, split};
+      a.tiles = lc.gd.tiles;
+      launch_any<v4f>(kind, mode, U, nt, lc, a);
+      GG_HIP_TRY(hipGetLastError());
+    }
+    if (edge > 0) {
+      a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
+      launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, loads), s, &pt, ca, split};
+      a.tiles = lc.gd.tiles;
+      launch_any<float>(kind, mode, 1, nt, lc, a);
+      GG_HIP_TRY(hipGetLastError());
+    }
   }
   return GG_OK;
 }

@@ -38,6 +38,7 @@ struct gg_tuning {
   int32_t chunks;         // access-type items per thread per tile: 1, 2, 4, 8
   int32_t blocks_per_cu;  // 0: no cap; >0: at most this many resident workgroups per CU (LDS reservation)
   int32_t nontemporal;    // 1: streaming (nt) loads and stores
+  int32_t hop_group;      // dissemination: hops per launch on long cycles (0: never split)
 };
 
 struct gg_ctx {
@@ -53,6 +54,8 @@ struct gg_ctx {
   // shuffle state
   int32_t* d_scratch;           // device int32[scratch_cap]
   int64_t scratch_cap;
+  float* d_carry;               // dissemination: parking column(s) of split cycle walks
+  int64_t carry_cap;            // in floats
   int64_t* d_offsets;           // device int64[p+1]
   int64_t* h_offsets_pinned;    // pinned staging for the upload
   std::vector<int64_t> offsets_cached;

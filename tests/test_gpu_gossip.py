@@ -95,6 +95,16 @@ def test_dissemination_data_path(mode, p, n, stride):
     _check(p, n, stride, 2 * sc.num_phases(p) + 2, seed=6, topology=gg.TOPO_DISSEMINATION, **mode)
 
 
+@pytest.mark.parametrize("hop_group", [0, 2, 3, 8, 32])
+@pytest.mark.parametrize("mode", [dict(), dict(staleness=1), dict(avg_mode=gg.AVG_GRAD),
+                                  dict(staleness=1, double_buffer=True), dict(double_buffer=True)])
+@pytest.mark.parametrize("p,n,stride", [(64, 20_003, 20_004), (12, 5_001, 5_001), (7, 3_000, 3_000)])
+def test_dissemination_hop_groups_never_change_results(hop_group, mode, p, n, stride):
+    # long partner cycles walked in groups of hops (one launch per group, last group first)
+    _check(p, n, stride, sc.num_phases(p) + 2, seed=16, topology=gg.TOPO_DISSEMINATION,
+           tune={gg.TUNE_HOP_GROUP: hop_group}, **mode)
+
+
 @pytest.mark.parametrize("tune", [
     {gg.TUNE_THREADS: 64, gg.TUNE_CHUNKS: 1}, {gg.TUNE_THREADS: 128, gg.TUNE_CHUNKS: 4},
     {gg.TUNE_THREADS: 256, gg.TUNE_CHUNKS: 8}, {gg.TUNE_BLOCKS_PER_CU: 0, gg.TUNE_CHUNKS: 2}, {gg.TUNE_BLOCKS_PER_CU: 3},
