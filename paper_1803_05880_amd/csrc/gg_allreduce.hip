@@ -18,24 +18,6 @@ struct ar_args {
   int32_t scaled;
 };
 
-__device__ __forceinline__ int64_t item_index(const gg_range& r, int64_t x) {
-  int64_t i = r.lo + x;
-  if (i >= r.gap_at) i += r.gap_len;
-  return i;
-}
-
-template <bool NT, typename V>
-__device__ __forceinline__ V ld(const V* ptr) {
-  if (NT) return __builtin_nontemporal_load(ptr);
-  return *ptr;
-}
-template <bool NT, typename V>
-__device__ __forceinline__ void st(V* ptr, V val) {
-  if (NT)
-    __builtin_nontemporal_store(val, ptr);
-  else
-    *ptr = val;
-}
 
 // One round: ranks j and j ^ shift both end with g[j] + g[j ^ shift].  A thread
 // owns the same chunk of both, so the round is in place: 8 B / rank / element.
@@ -57,10 +39,10 @@ __global__ void __launch_bounds__(256) allreduce_round_kernel(ar_args a) {
     for (int u = 0; u < U; ++u) {
       const int64_t x = x0 + (int64_t)u * blockDim.x;
       on[u] = x < a.rng.count;
-      idx[u] = item_index(a.rng, x);
+      idx[u] = gg_item_index(a.rng, x);
       if (on[u]) {
-        A[u] = ld<NT>(gj + idx[u]);
-        B[u] = ld<NT>(gc + idx[u]);
+        A[u] = gg_ld<NT>(gj + idx[u]);
+        B[u] = gg_ld<NT>(gc + idx[u]);
       }
     }
 #pragma unroll
@@ -68,8 +50,8 @@ __global__ void __launch_bounds__(256) allreduce_round_kernel(ar_args a) {
       if (!on[u]) continue;
       V s = A[u] + B[u];
       if (a.scaled) s = s * a.scale;
-      st<NT>(gj + idx[u], s);
-      st<NT>(gc + idx[u], s);
+      gg_st<NT>(gj + idx[u], s);
+      gg_st<NT>(gc + idx[u], s);
     }
   }
 }
@@ -87,7 +69,7 @@ struct tree_sum {
 template <typename V, bool NT>
 struct tree_sum<0, V, NT> {
   static __device__ __forceinline__ V run(const float* g, int64_t stride, int64_t i, int64_t r) {
-    return ld<NT>(reinterpret_cast<const V*>(g + r * stride) + i);
+    return gg_ld<NT>(reinterpret_cast<const V*>(g + r * stride) + i);
   }
 };
 
@@ -98,10 +80,10 @@ __global__ void __launch_bounds__(256) allreduce_onepass_kernel(ar_args a) {
   for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
     const int64_t x = tile * blockDim.x + threadIdx.x;
     if (x >= a.rng.count) continue;
-    const int64_t i = item_index(a.rng, x);
+    const int64_t i = gg_item_index(a.rng, x);
     V s = tree_sum<K, V, NT>::run(a.g, a.stride, i, 0);
     if (a.scaled) s = s * a.scale;
-    for (int64_t r = 0; r < (int64_t(1) << K); ++r) st<NT>(reinterpret_cast<V*>(a.g + r * a.stride) + i, s);
+    for (int64_t r = 0; r < (int64_t(1) << K); ++r) gg_st<NT>(reinterpret_cast<V*>(a.g + r * a.stride) + i, s);
   }
 }
 

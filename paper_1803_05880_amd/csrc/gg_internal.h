@@ -33,6 +33,28 @@ struct gg_range {
   int64_t gap_len;
 };
 
+// ---- device helpers shared by the streaming kernels
+// Nothing these kernels touch is read twice, so loads and stores carry the
+// non-temporal hint (NT) unless it is switched off for comparison.
+template <bool NT, typename V>
+__device__ __forceinline__ V gg_ld(const V* ptr) {
+  if (NT) return __builtin_nontemporal_load(ptr);
+  return *ptr;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void gg_st(V* ptr, V val) {
+  if (NT)
+    __builtin_nontemporal_store(val, ptr);
+  else
+    *ptr = val;
+}
+// Work item x of a range -> index in units of the access type (skips the hole).
+__device__ __forceinline__ int64_t gg_item_index(const gg_range& r, int64_t x) {
+  int64_t i = r.lo + x;
+  if (i >= r.gap_at) i += r.gap_len;
+  return i;
+}
+
 struct gg_tuning {
   int32_t threads;        // workgroup size
   int32_t chunks;         // access-type items per thread per tile: 1, 2, 4, 8

@@ -135,3 +135,41 @@ def test_compute_entry_points_fail_loudly_without_a_gpu():
     with pytest.raises(TypeError):
         ctx.sgd_step(torch.zeros(32), torch.zeros(32), torch.zeros(32))   # CPU tensors are refused
     ctx.close()
+
+
+def test_probe_entry_points_validate_arguments():
+    L = gg.lib()
+    E = gg.binding
+    assert L.gg_copy_probe(None, ctypes.c_void_p(256), 16, None) == E.GG_ERR_ARG
+    assert L.gg_copy_probe(ctypes.c_void_p(256), ctypes.c_void_p(512), 24, None) == E.GG_ERR_ARG
+    assert L.gg_copy_probe(ctypes.c_void_p(260), ctypes.c_void_p(512), 16, None) == E.GG_ERR_ALIGN
+    assert L.gg_copy_probe(ctypes.c_void_p(256), ctypes.c_void_p(512), 0, None) == 0
+    assert L.gg_busy_probe(10, 0, ctypes.c_void_p(256), None) == E.GG_ERR_ARG
+    assert L.gg_busy_probe(-1, 4, ctypes.c_void_p(256), None) == E.GG_ERR_ARG
+    assert L.gg_busy_probe(10, 4, None, None) == E.GG_ERR_ARG
+    ctx = gg.Context(p=4, n=8)
+    assert L.gg_set_tuning(ctx._h, 4, 1) == E.GG_ERR_ARG and L.gg_set_tuning(ctx._h, 4, 0) == 0
+    assert L.gg_set_tuning(ctx._h, 2, 2) == E.GG_ERR_ARG and L.gg_set_tuning(ctx._h, 2, 3) == 0
+    off = np.array([0, 2, 4, 6, 8], np.int64).ctypes.data_as(ctypes.c_void_p)
+    assert L.gg_shuffle_payload(ctx._h, 0, ctypes.c_void_p(256), 6, off, 1, None) == E.GG_ERR_ARG    # not a multiple of 4
+    assert L.gg_shuffle_payload(ctx._h, 0, ctypes.c_void_p(256), 8, off, 3, None) == E.GG_ERR_ARG    # batch > min n_j
+    assert L.gg_shuffle_payload(ctx._h, -1, ctypes.c_void_p(256), 8, off, 1, None) == E.GG_ERR_ARG
+    ctx.close()
+
+
+def test_partner_matches_oracle_on_random_configurations():
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None)
+    @given(st.integers(2, 200), st.integers(0, 2**64 - 1), st.integers(0, 10**12), st.integers(1, 7),
+           st.sampled_from([gg.TOPO_HYPERCUBE, gg.TOPO_DISSEMINATION]))
+    def check(p, seed, step, num_comms, topology):
+        if topology == gg.TOPO_HYPERCUBE:
+            p = 1 << max(1, p.bit_length() % 8)
+        ctx = gg.Context(p=p, n=1, seed=seed, topology=topology, num_comms=num_comms)
+        send, recv = ctx.partner(step)
+        o_send, o_recv = sc.partners(p, seed, num_comms, topology, step)
+        ctx.close()
+        assert send.tolist() == o_send and recv.tolist() == o_recv
+
+    check()
