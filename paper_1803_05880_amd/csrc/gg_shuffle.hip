@@ -28,49 +28,69 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lan
   return x;
 }
 
-// Flag the slots of one rank (4 consecutive slots per thread per tile: one Philox
-// block), and write the flagged slot numbers to sel[base ..] in ascending order:
-// per-thread popcount -> wavefront prefix -> prefix over the 16 wave totals in
-// LDS -> ordered scatter.  Returns the number of flagged slots (same in every
-// thread).
+// Flags of the 4 consecutive slots a thread owns in the tile that starts at tile0
+// (one Philox block); slots beyond the rank's end are never flagged.
+__device__ __forceinline__ uint32_t tile_flags(const swap_args& a, uint32_t rank, int64_t n_r, int64_t tile0,
+                                               uint32_t f[4]) {
+  const int64_t slot0 = tile0 + (int64_t)threadIdx.x * SLOTS_PER_THREAD;
+  f[0] = f[1] = f[2] = f[3] = 0;
+  if (slot0 < n_r) {
+    const gg_u32x4 o = gg_philox4x32_10((uint32_t)(slot0 >> 2), rank, a.step32, (uint32_t)GG_TAG_SHUF, a.k0, a.k1);
+    f[0] = (o.x >> 29) == 0;
+    f[1] = (o.y >> 29) == 0 && slot0 + 1 < n_r;
+    f[2] = (o.z >> 29) == 0 && slot0 + 2 < n_r;
+    f[3] = (o.w >> 29) == 0 && slot0 + 3 < n_r;
+  }
+  return f[0] + f[1] + f[2] + f[3];
+}
+
+// Exclusive prefix of one count per thread over the 1024-thread workgroup
+// (wavefront prefix, then a prefix over the 16 wave totals in LDS).  Returns the
+// thread's offset and the workgroup total; ends with a barrier so the LDS words can
+// be reused at once.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t cnt, uint32_t* s_wave, uint32_t* s_total,
+                                                         uint32_t* total) {
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_inclusive_scan(cnt, lane);
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  if (wave == 0) {
+    const uint32_t t = lane < SWAP_WAVES ? s_wave[lane] : 0u;
+    const uint32_t ti = wave_inclusive_scan(t, lane);
+    if (lane < SWAP_WAVES) s_wave[lane] = ti - t;  // exclusive offset of each wave
+    if (lane == SWAP_WAVES - 1) *s_total = ti;
+  }
+  __syncthreads();
+  const uint32_t offset = s_wave[wave] + (incl - cnt);
+  *total = *s_total;
+  __syncthreads();
+  return offset;
+}
+
+// Flag the slots of one rank tile by tile and write the flagged slot numbers to
+// sel_r[0 ..] in ascending order (per-thread popcount -> prefix -> ordered
+// scatter).  Returns the number of flagged slots (same in every thread).
 __device__ uint32_t compact_flagged(const swap_args& a, uint32_t rank, int64_t n_r, int32_t* sel_r,
                                     uint32_t* s_wave, uint32_t* s_total) {
-  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   uint32_t running = 0;
   const int64_t per_tile = (int64_t)SWAP_THREADS * SLOTS_PER_THREAD;
   for (int64_t tile0 = 0; tile0 < n_r; tile0 += per_tile) {
-    const int64_t slot0 = tile0 + (int64_t)tid * SLOTS_PER_THREAD;
-    uint32_t f[4] = {0, 0, 0, 0};
-    if (slot0 < n_r) {
-      const gg_u32x4 o = gg_philox4x32_10((uint32_t)(slot0 >> 2), rank, a.step32, (uint32_t)GG_TAG_SHUF, a.k0, a.k1);
-      f[0] = (o.x >> 29) == 0;
-      f[1] = (o.y >> 29) == 0 && slot0 + 1 < n_r;
-      f[2] = (o.z >> 29) == 0 && slot0 + 2 < n_r;
-      f[3] = (o.w >> 29) == 0 && slot0 + 3 < n_r;
-    }
-    const uint32_t cnt = f[0] + f[1] + f[2] + f[3];
-    const uint32_t incl = wave_inclusive_scan(cnt, lane);
-    if (lane == 63) s_wave[wave] = incl;
-    __syncthreads();
-    if (wave == 0) {
-      const uint32_t t = lane < SWAP_WAVES ? s_wave[lane] : 0u;
-      const uint32_t ti = wave_inclusive_scan(t, lane);
-      if (lane < SWAP_WAVES) s_wave[lane] = ti - t;  // exclusive offset of each wave
-      if (lane == SWAP_WAVES - 1) *s_total = ti;
-    }
-    __syncthreads();
-    uint32_t pos = running + s_wave[wave] + (incl - cnt);
+    uint32_t f[4], total;
+    const uint32_t cnt = tile_flags(a, rank, n_r, tile0, f);
+    uint32_t pos = running + block_exclusive_scan(cnt, s_wave, s_total, &total);
+    const int64_t slot0 = tile0 + (int64_t)threadIdx.x * SLOTS_PER_THREAD;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       if (f[e]) sel_r[pos++] = (int32_t)(slot0 + e);
-    running += *s_total;
-    __syncthreads();  // s_wave / s_total are rewritten by the next tile
+    running += total;
   }
   return running;
 }
 
 // One workgroup per partner pair (j, c): compact both ranks' flagged slots, then
-// swap the r-th flagged slot of j with the r-th flagged slot of c.
+// swap the r-th flagged slot of j with the r-th flagged slot of c.  Used while a
+// rank holds few tiles; beyond that the three kernels below spread the tiles over
+// the chip.
 __global__ void __launch_bounds__(SWAP_THREADS) partner_swap_kernel(swap_args a) {
   __shared__ uint32_t s_wave[SWAP_WAVES];
   __shared__ uint32_t s_total;
@@ -88,6 +108,71 @@ __global__ void __launch_bounds__(SWAP_THREADS) partner_swap_kernel(swap_args a)
   __syncthreads();  // the sel lists written above are read by other threads below
   const uint32_t m = cnt_j < cnt_c ? cnt_j : cnt_c;
   for (uint32_t r = threadIdx.x; r < m; r += SWAP_THREADS) {
+    int32_t* pa = a.idx + off_j + sel_j[r];
+    int32_t* pb = a.idx + off_c + sel_c[r];
+    const int32_t va = *pa, vb = *pb;
+    *pa = vb;
+    *pb = va;
+  }
+}
+
+// ---- the same shuffle for ranks with many tiles: count, scatter, swap
+// tile_counts[rank * max_tiles + tile] = flagged slots in that tile.
+__global__ void __launch_bounds__(SWAP_THREADS) swap_count_kernel(swap_args a, uint32_t* tile_counts,
+                                                                  int32_t max_tiles) {
+  __shared__ uint32_t s_wave[SWAP_WAVES];
+  __shared__ uint32_t s_total;
+  const uint32_t rank = blockIdx.y, tile = blockIdx.x;
+  const int64_t n_r = a.off[rank + 1] - a.off[rank];
+  uint32_t f[4], total;
+  const uint32_t cnt = tile_flags(a, rank, n_r, (int64_t)tile * SWAP_THREADS * SLOTS_PER_THREAD, f);
+  (void)block_exclusive_scan(cnt, s_wave, &s_total, &total);
+  if (threadIdx.x == 0) tile_counts[(int64_t)rank * max_tiles + tile] = total;
+}
+
+// Sum of counts[0 .. n) by the whole workgroup (n is small: tiles of one rank).
+__device__ __forceinline__ uint32_t block_sum(const uint32_t* counts, int32_t n, uint32_t* s_wave, uint32_t* s_total) {
+  uint32_t part = 0, total;
+  for (int32_t i = threadIdx.x; i < n; i += SWAP_THREADS) part += counts[i];
+  (void)block_exclusive_scan(part, s_wave, s_total, &total);
+  return total;
+}
+
+__global__ void __launch_bounds__(SWAP_THREADS) swap_scatter_kernel(swap_args a, const uint32_t* tile_counts,
+                                                                    int32_t max_tiles) {
+  __shared__ uint32_t s_wave[SWAP_WAVES];
+  __shared__ uint32_t s_total;
+  const uint32_t rank = blockIdx.y, tile = blockIdx.x;
+  const int64_t n_r = a.off[rank + 1] - a.off[rank];
+  const int64_t tile0 = (int64_t)tile * SWAP_THREADS * SLOTS_PER_THREAD;
+  if (tile0 >= n_r) return;  // uniform for the workgroup
+  const uint32_t base = block_sum(tile_counts + (int64_t)rank * max_tiles, (int32_t)tile, s_wave, &s_total);
+  uint32_t f[4], total;
+  const uint32_t cnt = tile_flags(a, rank, n_r, tile0, f);
+  uint32_t pos = base + block_exclusive_scan(cnt, s_wave, &s_total, &total);
+  int32_t* sel_r = a.sel + a.off[rank];
+  const int64_t slot0 = tile0 + (int64_t)threadIdx.x * SLOTS_PER_THREAD;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (f[e]) sel_r[pos++] = (int32_t)(slot0 + e);
+}
+
+__global__ void __launch_bounds__(SWAP_THREADS) swap_apply_kernel(swap_args a, const uint32_t* tile_counts,
+                                                                  int32_t max_tiles) {
+  __shared__ uint32_t s_wave[SWAP_WAVES];
+  __shared__ uint32_t s_total;
+  const int32_t q = blockIdx.y;
+  const int32_t low = a.shift - 1;
+  const int32_t v0 = ((q & ~low) << 1) | (q & low);
+  const uint32_t j = a.sigma[v0];
+  const uint32_t c = a.sigma[v0 | a.shift];
+  const uint32_t cnt_j = block_sum(tile_counts + (int64_t)j * max_tiles, max_tiles, s_wave, &s_total);
+  const uint32_t cnt_c = block_sum(tile_counts + (int64_t)c * max_tiles, max_tiles, s_wave, &s_total);
+  const uint32_t m = cnt_j < cnt_c ? cnt_j : cnt_c;
+  const int64_t off_j = a.off[j], off_c = a.off[c];
+  const int32_t* sel_j = a.sel + off_j;
+  const int32_t* sel_c = a.sel + off_c;
+  for (uint32_t r = blockIdx.x * SWAP_THREADS + threadIdx.x; r < m; r += gridDim.x * SWAP_THREADS) {
     int32_t* pa = a.idx + off_j + sel_j[r];
     int32_t* pb = a.idx + off_c + sel_c[r];
     const int32_t va = *pa, vb = *pb;
@@ -150,9 +235,8 @@ __global__ void __launch_bounds__(256) ring_payload_kernel(ring_args a, Wd* payl
 }
 
 // Make the device copy of rank_offsets current and the scratch large enough.
-int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s, bool need_scratch) {
+int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s, int64_t scratch_words) {
   const int32_t p = ctx->cfg.p;
-  const int64_t n_total = off[p];
   if (!ctx->d_offsets) {
     if (hipMalloc((void**)&ctx->d_offsets, (size_t)(p + 1) * sizeof(int64_t)) != hipSuccess ||
         hipHostMalloc((void**)&ctx->h_offsets_pinned, (size_t)(p + 1) * sizeof(int64_t), hipHostMallocDefault) !=
@@ -170,16 +254,16 @@ int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s, bool need_scratch) {
                               hipMemcpyHostToDevice, s));
     ctx->offsets_cached.assign(off, off + p + 1);
   }
-  if (need_scratch && n_total > ctx->scratch_cap) {
+  if (scratch_words > ctx->scratch_cap) {
     GG_HIP_TRY(hipDeviceSynchronize());
     if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
     ctx->d_scratch = nullptr;
     ctx->scratch_cap = 0;
-    if (hipMalloc((void**)&ctx->d_scratch, (size_t)n_total * sizeof(int32_t)) != hipSuccess) {
+    if (hipMalloc((void**)&ctx->d_scratch, (size_t)scratch_words * sizeof(int32_t)) != hipSuccess) {
       (void)hipGetLastError();
       return GG_ERR_NOMEM;
     }
-    ctx->scratch_cap = n_total;
+    ctx->scratch_cap = scratch_words;
   }
   return GG_OK;
 }
@@ -193,11 +277,12 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
   if (!gg_aligned(idx, 4)) return GG_ERR_ALIGN;
   const int32_t p = ctx->cfg.p;
   if (rank_offsets[0] != 0) return GG_ERR_ARG;
-  int64_t min_n = INT64_MAX;
+  int64_t min_n = INT64_MAX, max_n = 0;
   for (int32_t j = 0; j < p; ++j) {
     const int64_t n_j = rank_offsets[j + 1] - rank_offsets[j];
     if (n_j < 0 || n_j > 0x7fffffffLL) return GG_ERR_ARG;
     if (n_j < min_n) min_n = n_j;
+    if (n_j > max_n) max_n = n_j;
   }
   if (rank_offsets[p] > (int64_t(1) << 34)) return GG_ERR_ARG;
   if (mode == GG_SHUF_PARTNER_SWAP) {
@@ -209,7 +294,11 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
   if (rc != GG_OK) return rc;
   if (rank_offsets[p] == 0) return GG_OK;
   hipStream_t s = (hipStream_t)stream;
-  rc = prepare(ctx, rank_offsets, s, true);
+  // scratch: flagged-slot lists (one word per slot at most), then per-tile counts
+  const int64_t per_tile = (int64_t)SWAP_THREADS * SLOTS_PER_THREAD;
+  const int32_t max_tiles = (int32_t)((max_n + per_tile - 1) / per_tile);
+  const int64_t counts_at = (rank_offsets[p] + 3) / 4 * 4;
+  rc = prepare(ctx, rank_offsets, s, counts_at + (int64_t)p * (max_tiles > 0 ? max_tiles : 1));
   if (rc != GG_OK) return rc;
 
   if (mode == GG_SHUF_PARTNER_SWAP) {
@@ -224,8 +313,21 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
     a.step32 = (uint32_t)((uint64_t)step & 0xffffffffu);
     a.k0 = (uint32_t)ctx->cfg.seed;
     a.k1 = (uint32_t)(ctx->cfg.seed >> 32);
-    hipLaunchKernelGGL(partner_swap_kernel, dim3(p / 2), dim3(SWAP_THREADS), 0, s, a);
-    GG_HIP_TRY(hipGetLastError());
+    if (max_tiles <= 8) {
+      // few tiles per rank: one workgroup per pair does everything in one launch
+      hipLaunchKernelGGL(partner_swap_kernel, dim3(p / 2), dim3(SWAP_THREADS), 0, s, a);
+      GG_HIP_TRY(hipGetLastError());
+    } else {
+      uint32_t* counts = reinterpret_cast<uint32_t*>(ctx->d_scratch + counts_at);
+      hipLaunchKernelGGL(swap_count_kernel, dim3(max_tiles, p), dim3(SWAP_THREADS), 0, s, a, counts, max_tiles);
+      GG_HIP_TRY(hipGetLastError());
+      hipLaunchKernelGGL(swap_scatter_kernel, dim3(max_tiles, p), dim3(SWAP_THREADS), 0, s, a, counts, max_tiles);
+      GG_HIP_TRY(hipGetLastError());
+      int64_t bx = max_n / (8 * SWAP_THREADS) + 1;  // about one thread per expected swap
+      if (bx > 4096) bx = 4096;
+      hipLaunchKernelGGL(swap_apply_kernel, dim3((unsigned)bx, p / 2), dim3(SWAP_THREADS), 0, s, a, counts, max_tiles);
+      GG_HIP_TRY(hipGetLastError());
+    }
   } else {
     if (batch == 0) return GG_OK;
     ring_args a;
@@ -263,7 +365,7 @@ extern "C" int gg_shuffle_payload(gg_ctx* ctx, int64_t step, void* payload, int6
   if (rc != GG_OK) return rc;
   if (batch == 0) return GG_OK;
   hipStream_t s = (hipStream_t)stream;
-  rc = prepare(ctx, rank_offsets, s, false);
+  rc = prepare(ctx, rank_offsets, s, 0);
   if (rc != GG_OK) return rc;
   ring_args a;
   a.idx = nullptr;

@@ -34,11 +34,14 @@ def test_partner_swap_bit_exact(p, n_total):
     ctx.close()
 
 
-def test_partner_swap_uneven_and_empty_ranks():
+@pytest.mark.parametrize("off", [[0, 0, 5000, 5003, 20_000],            # one workgroup per pair
+                                 [0, 0, 70_000, 70_003, 200_000],       # many tiles per rank: count/scatter/swap kernels
+                                 [0, 40_961, 40_961, 81_922, 81_923]])
+def test_partner_swap_uneven_and_empty_ranks(off):
     p = 4
-    off = np.array([0, 0, 5000, 5003, 20_000], dtype=np.int64)       # an empty rank, a tiny one
-    idx_o = sh.initial_indices(20_000)
-    idx_g = gg_synth.make_indices(20_000, DEV)
+    off = np.array(off, dtype=np.int64)                              # an empty rank, a tiny one
+    idx_o = sh.initial_indices(int(off[-1]))
+    idx_g = gg_synth.make_indices(int(off[-1]), DEV)
     ctx = gg.Context(p=p, n=4, seed=3)
     for t in range(6):
         c, _ = sc.partners(p, 3, p, sc.HYPERCUBE, t)
