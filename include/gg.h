@@ -65,7 +65,8 @@ typedef struct {
   int32_t topology;    /* GG_TOPO_*                                                        */
   int64_t n;           /* fp32 parameters per rank, >= 0                                   */
   int64_t rank_stride; /* elements between consecutive ranks in every [p][.] buffer, >= n  */
-  int32_t num_comms;   /* R, shuffled communicators: 1 = no rotation, 0 = p (Sec. 4.5.1)   */
+  int32_t num_comms;   /* R, shuffled communicators: 1 = no rotation, 0 = p (Sec. 4.5.1);
+                          at most 4096                                                     */
   int32_t avg_mode;    /* GG_AVG_*: what is averaged with the partner                      */
   int32_t staleness;   /* 0: partner's post-update weights of this step (Sec. 6);
                           1: partner's weights as they stood on entry to this step

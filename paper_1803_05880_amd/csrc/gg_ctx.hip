@@ -87,7 +87,7 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
     return GG_ERR_ARG;
   if (cfg->staleness != 0 && cfg->staleness != 1) return GG_ERR_ARG;
   if (cfg->staleness == 1 && cfg->avg_mode != GG_AVG_MODEL) return GG_ERR_ARG;
-  if (cfg->num_comms < 0 || cfg->num_comms > 65536 || cfg->reserved != 0) return GG_ERR_ARG;
+  if (cfg->num_comms < 0 || cfg->num_comms > 4096 || cfg->reserved != 0) return GG_ERR_ARG;
   if (!(cfg->lr == cfg->lr) || !(cfg->momentum == cfg->momentum)) return GG_ERR_ARG;  // NaN
   if (cfg->topology == GG_TOPO_HYPERCUBE && !gg_is_pow2(cfg->p)) return GG_ERR_NOT_POW2;
 

@@ -95,6 +95,7 @@ def test_init_argument_validation():
     assert _init_code(staleness=2) == gg.binding.GG_ERR_ARG
     assert _init_code(staleness=1, avg_mode=1) == gg.binding.GG_ERR_ARG
     assert _init_code(num_comms=-1) == gg.binding.GG_ERR_ARG
+    assert _init_code(num_comms=4097) == gg.binding.GG_ERR_ARG
     assert _init_code(reserved=1) == gg.binding.GG_ERR_ARG
     assert _init_code(lr=float("nan")) == gg.binding.GG_ERR_ARG
     assert gg.lib().gg_init(None, None) == gg.binding.GG_ERR_ARG

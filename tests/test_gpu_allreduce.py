@@ -16,7 +16,7 @@ DEV = "cuda:0"
 @pytest.mark.parametrize("form", ["baseline", "onepass"])
 @pytest.mark.parametrize("average", [True, False])
 @pytest.mark.parametrize("p,n,stride", [(2, 5, 5), (4, 100_003, 100_004), (8, 262_151, 262_152), (16, 70_001, 70_001),
-                                        (64, 10_000, 10_000), (128, 4_100, 4_100), (256, 1_031, 1_032)])
+                                        (64, 10_000, 10_000), (128, 4_100, 4_100), (256, 1_031, 1_032), (1024, 515, 516)])
 def test_allreduce_matches_oracle_bitwise(form, average, p, n, stride):
     _, G, _ = host_state(p, n, stride, seed=11)
     G[:, n:] = 5.0

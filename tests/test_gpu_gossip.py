@@ -116,6 +116,13 @@ def test_launch_shapes_never_change_results(tune):
     _check(8, 200_001, 200_004, 3, seed=7, tune=tune, topology=gg.TOPO_DISSEMINATION)
 
 
+@pytest.mark.parametrize("topology,p", [(gg.TOPO_HYPERCUBE, 1024), (gg.TOPO_DISSEMINATION, 1024),
+                                        (gg.TOPO_DISSEMINATION, 1000)])
+def test_maximum_rank_count(topology, p):
+    # GG_MAX_RANKS virtual ranks: full pair table / longest cycles, a rotated communicator included
+    _check(p, 1_027, 1_028, 3, seed=17, first_step=sc.num_phases(p) - 1, topology=topology)
+
+
 def test_late_steps_and_rotation_wrap():
     p = 8
     L = 3
