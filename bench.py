@@ -268,6 +268,7 @@ def main():
             "traffic": pmc_traffic_bytes(args.workload),
             "algorithmic_bytes_per_launch": algo_bytes,
             "kernel_ms_avg": round(k_avg, 4),
+            "kernel_ms_med": round(sorted(k_ms)[len(k_ms) // 2], 4),
             "kernel_ms_min": round(min(k_ms), 4),
         },
     }
@@ -320,6 +321,7 @@ def main():
         _, pr = time_loop(torch, cp, reps, 2)
         cp_ms = sum(event_ms(pr)) / len(pr)
         extras["copy_kernel_GBps"] = round(2.0 * 4 * p * stride / (cp_ms * 1e-3) / 1e9, 1)
+        extras["gossip_pct_of_copy_kernel"] = round(100.0 * achieved / extras["copy_kernel_GBps"], 1)
 
         # staleness-1 variant with a double buffer (scratch doubles as the second w)
         ctx_s = gg.Context(p=p, n=n, rank_stride=stride, seed=0, lr=lr, momentum=mu, staleness=1)
