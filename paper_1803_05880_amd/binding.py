@@ -2,7 +2,7 @@
 
 Every step of the path runs in the library's HIP kernels; there is no CPU or
 PyTorch fallback.  Importing this module fails loudly when libgg.so has not
-been built (python -m paper_1803_05880_amd.build).  Tensors are torch CUDA
+been built and cannot be built (python -m paper_1803_05880_amd.build).  Tensors are torch CUDA
 tensors used as device memory; the stream is torch's current stream unless
 one is given.
 """
@@ -54,7 +54,14 @@ def lib():
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
-            raise ImportError("libgg.so is not built: run `python -m paper_1803_05880_amd.build`")
+            # nothing built yet: compile once (hipcc cross-compiles without a GPU); there is
+            # no other implementation to fall back to, so a failed build is fatal
+            try:
+                from .build import build_library
+                build_library()
+            except Exception as exc:
+                raise ImportError("libgg.so is not built and building it failed (%s): run "
+                                  "`python -m paper_1803_05880_amd.build`" % exc)
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         L.gg_init.argtypes = [ctypes.POINTER(GGConfig), ctypes.POINTER(vp)]
