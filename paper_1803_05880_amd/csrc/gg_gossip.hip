@@ -586,6 +586,10 @@ extern "C" int gg_gossip_step(gg_ctx* ctx, int64_t step, float* w, const float* 
     mode = MODE_SYNC;
   } else {
     kind = cfg.topology == GG_TOPO_HYPERCUBE ? KIND_PAIR : KIND_CYCLE;
+    // Dissemination with shift p/2: receiving from v - p/2 is receiving from v + p/2, the
+    // map is an involution and its 2-cycles are exactly the pairs (v, v | p/2) -- same
+    // arithmetic (the sum of the two contributions commutes), faster kernel.
+    if (kind == KIND_CYCLE && 2 * a.shift == cfg.p) kind = KIND_PAIR;
     mode = cfg.avg_mode == GG_AVG_GRAD ? MODE_GRAD : (cfg.staleness ? MODE_STALE : MODE_SYNC);
   }
   return enqueue_step(ctx, kind, mode, a, &ctx->sigma[(size_t)r * cfg.p], e_lo, e_hi, (hipStream_t)stream);
