@@ -3,7 +3,8 @@
 
 One "step" is one pass of the whole hot path for all p virtual ranks: the
 partner schedule lookup, the fused momentum-SGD update + pairwise model average
-(one launch) and the partner-swap shuffle of the sample indices (one launch).
+(one launch) and the partner-swap shuffle of the sample indices (on a second
+stream, beside the update).
 Inputs are synthetic and resident in HBM before the timed region starts.
 
 Workload (default): p = 64 virtual ranks x N = 25,557,032 fp32 parameters
@@ -228,8 +229,13 @@ def main():
             ctx.gossip_step(t, W, G, M)
             b.record(stream)
             pairs.append((a, b))
-        ctx.shuffle(t, gg.SHUF_PARTNER_SWAP, idx, off)
+        # the index shuffle does not depend on the parameter update: it runs beside it on
+        # its own stream (the paper overlaps the sample rotation with computation, Sec. 5)
+        ctx.shuffle(t, gg.SHUF_PARTNER_SWAP, idx, off, stream=side_stream)
 
+    side_stream = torch.cuda.Stream()
+    ctx.shuffle(0, gg.SHUF_PARTNER_SWAP, idx, off)      # first use allocates the library's scratch
+    torch.cuda.synchronize()
     ms_step, pairs = time_loop(torch, full_step, args.steps, args.warmup)
     k_ms = event_ms(pairs)
     k_avg = sum(k_ms) / len(k_ms)
