@@ -207,3 +207,33 @@ def test_argument_errors_on_device():
     torch.cuda.synchronize()
     assert (w == 0).all() and (m == 0).all()
     ctx.close()
+
+
+def test_calls_follow_the_stream_they_are_given():
+    # steps issued on two user streams chained by events must equal the single-stream run
+    p, n = 8, 400_000
+    W, G, M = host_state(p, n, n, seed=18)
+    ref_w, ref_m = _run_gpu(W, G, M, n, n, p, 18, 6)
+    ctx = gg.Context(p=p, n=n, rank_stride=n, seed=18, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM)
+    w, g, m = W.to(DEV), G.to(DEV), M.to(DEV)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    prev = None
+    for t in range(6):
+        s = streams[t & 1]
+        if prev is not None:
+            s.wait_event(prev)
+        ctx.gossip_step(t, w, g, m, stream=s)
+        prev = torch.cuda.Event()
+        prev.record(s)
+    torch.cuda.synchronize()
+    assert torch.equal(w.cpu(), ref_w) and torch.equal(m.cpu(), ref_m)
+    ctx.close()
+
+
+def test_repeated_calls_are_deterministic():
+    p, n = 16, 123_457
+    W, G, M = host_state(p, n, n + 3, seed=19)
+    a = _run_gpu(W, G, M, n, n + 3, p, 19, 5)
+    b = _run_gpu(W, G, M, n, n + 3, p, 19, 5)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
