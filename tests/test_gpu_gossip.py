@@ -237,3 +237,26 @@ def test_repeated_calls_are_deterministic():
     a = _run_gpu(W, G, M, n, n + 3, p, 19, 5)
     b = _run_gpu(W, G, M, n, n + 3, p, 19, 5)
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_step_can_be_captured_in_a_graph_and_replayed():
+    # the call only enqueues kernels (no allocation, no host state): a captured step replays
+    # to the same bits as eager calls of the same step, replay after replay
+    p, n = 8, 300_000
+    W, G, M = host_state(p, n, n, seed=20)
+    ctx = gg.Context(p=p, n=n, rank_stride=n, seed=20, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM)
+    w, g, m = W.to(DEV), G.to(DEV), M.to(DEV)
+    we, me = W.to(DEV), M.to(DEV)
+    ctx.gossip_step(4, we, g, me)                        # eager warm-up on its own buffers
+    we.copy_(w); me.copy_(m)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.gossip_step(4, w, g, m)
+    w.copy_(W.to(DEV)); m.copy_(M.to(DEV))               # capture does not execute; start from the inputs
+    for replay in range(3):
+        graph.replay()
+        ctx.gossip_step(4, we, g, me)
+        torch.cuda.synchronize()
+        assert torch.equal(w, we) and torch.equal(m, me), "replay %d" % replay
+    ctx.close()
