@@ -40,7 +40,7 @@ def test_config4_scale_out_shape_sampled_windows(staleness):
     p, n, seed = 64, gg_synth.RESNET50_PARAMS, 0
     stride = _bench_stride(n)
     W, G, M = gg_synth.make_state(p, n, stride, seed=seed, device=DEV)
-    cols = _columns(n, 48)
+    cols = _columns(n, 256)
     cd = torch.as_tensor(cols, device=DEV)
     Wo, Go, Mo = _take(W, cd), _take(G, cd), _take(M, cd)
     ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=seed, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM,
@@ -76,7 +76,7 @@ def test_config5_full_method_step_sampled_windows_and_shuffle():
     p, n, seed = 128, gg_synth.RESNET50_PARAMS, 0
     stride = _bench_stride(n)
     W, G, M = gg_synth.make_state(p, n, stride, seed=seed, device=DEV)
-    cols = _columns(n, 16)
+    cols = _columns(n, 256)
     cd = torch.as_tensor(cols, device=DEV)
     Wo, Go, Mo = _take(W, cd), _take(G, cd), _take(M, cd)
     off = sh.block_offsets(gg_synth.IMAGENET1K_TRAIN, p)
@@ -104,7 +104,7 @@ def test_config3_segments_and_allreduce_comparator_sampled_windows():
     seg, scales = gg_synth.segment_layout(n, 161, seed=seed)
     assert seg[0] == 0 and seg[-1] == n and len(seg) == 162 and (np.diff(seg) >= 1).all()
     W, G, M = gg_synth.make_state(p, n, stride, seed=seed, device=DEV, seg_offsets=seg, seg_scales=scales)
-    cols = _columns(n, 64)
+    cols = _columns(n, 256)
     cd = torch.as_tensor(cols, device=DEV)
     Wo, Go, Mo = _take(W, cd), _take(G, cd), _take(M, cd)
     Wa, Ga, Ma = W.clone(), G.clone(), M.clone()
