@@ -260,3 +260,13 @@ def test_step_can_be_captured_in_a_graph_and_replayed():
         torch.cuda.synchronize()
         assert torch.equal(w, we) and torch.equal(m, me), "replay %d" % replay
     ctx.close()
+
+
+def test_resume_with_a_fresh_context_continues_bit_exactly():
+    # the library keeps no step counter: a new context with the same seed resumes at any step
+    p, n = 8, 150_000
+    W, G, M = host_state(p, n, n, seed=21)
+    full_w, full_m = _run_gpu(W, G, M, n, n, p, 21, 7)
+    half_w, half_m = _run_gpu(W, G, M, n, n, p, 21, 3)
+    res_w, res_m = _run_gpu(half_w, G, half_m, n, n, p, 21, 4, first_step=3)
+    assert torch.equal(res_w, full_w) and torch.equal(res_m, full_m)
