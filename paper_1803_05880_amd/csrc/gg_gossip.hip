@@ -384,6 +384,28 @@ __global__ void __launch_bounds__(256) sgd_kernel(step_args a) {
   }
 }
 
+// Lean form for the default launch shape (see gossip_pair_lean_kernel).
+template <bool NT>
+__global__ void __launch_bounds__(64) sgd_lean_kernel(step_args a) {
+  const int64_t j = blockIdx.y;
+  const int64_t i = a.rng.lo + (int64_t)blockIdx.x * 64 + threadIdx.x;
+  if (i >= a.rng.lo + a.rng.count) return;
+  const v4f* w = reinterpret_cast<const v4f*>(a.w + j * a.stride) + i;
+  const v4f* g = reinterpret_cast<const v4f*>(a.g + j * a.stride) + i;
+  v4f* m = reinterpret_cast<v4f*>(a.m + j * a.stride) + i;
+  v4f* n = reinterpret_cast<v4f*>(a.wn + j * a.stride) + i;
+  const v4f Wr = gg_ld<NT>(w), Gr = gg_ld<NT>(g), Mr = gg_ld<NT>(m);
+  v4f v;
+  const v4f T = local_update(Wr, Gr, Mr, a.lr, a.mu, v);
+  if (NT) {
+    st_stream(n, T);
+    st_stream(m, v);
+  } else {
+    gg_st<false>(n, T);
+    gg_st<false>(m, v);
+  }
+}
+
 // ------------------------------------------------------------------------ dispatch
 enum { KIND_PAIR = 0, KIND_CYCLE = 1, KIND_SGD = 2 };
 
@@ -412,6 +434,8 @@ void launch_one(int kind, const launch_ctx& lc, const step_args& a) {
     else
       hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, (U > 2 ? 2 : U), NT, false>), gd.grid, gd.block, gd.lds_bytes,
                          s, a, lc.ca);
+  else if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles)
+    hipLaunchKernelGGL((sgd_lean_kernel<NT>), gd.grid, gd.block, gd.lds_bytes, s, a);
   else
     hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a);
 }
