@@ -28,7 +28,9 @@
  *   - All [p][.] buffers share one layout: rank j starts at element
  *     j * rank_stride, its n parameters are contiguous, rank_stride >= n.
  *     Buffers whose base address and rank_stride*4 are multiples of 16 bytes take
- *     the vector path; anything 4-byte aligned is accepted.
+ *     the vector path; anything 4-byte aligned is accepted.  For full bandwidth make
+ *     base addresses and rank_stride*4 multiples of 256 bytes (rank_stride a multiple
+ *     of 64): rows that start inside a 128-byte line cost about 13 %.
  *   - fp32 arithmetic, every multiply/add/subtract rounded on its own (no fused
  *     multiply-add), denormals kept.
  */
@@ -94,7 +96,10 @@ int gg_destroy(gg_ctx* ctx);
  * send_to: host int32[p], required.  recv_from: host int32[p] or NULL.  step >= 0. */
 int gg_partner(const gg_ctx* ctx, int64_t step, int32_t* send_to, int32_t* recv_from);
 
-/* One GossipGraD step for all p ranks (Eq. 1-2 + Sec. 6), fused in one launch:
+/* One GossipGraD step for all p ranks (Eq. 1-2 + Sec. 6), update and average fused
+ * (one launch; dissemination phases whose partner cycles are longer than 12 ranks
+ * take one launch per group of 8 hops, and the first such call allocates a
+ * context-owned carry column, which synchronises the device once):
  *     v = mu*m + lr*g ;  m <- v ;  T = w - v ;  w_new[j] = (T[j] + X[c(j)]) / 2
  * with c = the step's partner map (hypercube: the pair partner; dissemination:
  * the rank j receives from), X = T (staleness 0) or the entry weights w
@@ -126,7 +131,8 @@ int gg_allreduce_baseline(gg_ctx* ctx, float* g, int32_t average, void* stream);
 /* The same sum in one pass: each element's p values are read once, added in the
  * order of the recursive-doubling tree (bit-identical result) and written back to
  * every rank -- the bandwidth-optimal form available when all ranks share one
- * memory.  Same arguments as gg_allreduce_baseline. */
+ * memory.  Same arguments as gg_allreduce_baseline.  Above p = 128 it runs the
+ * rounds of gg_allreduce_baseline instead (same result). */
 int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void* stream);
 
 /* Rotation of sample indices (Sec. 4.5.2).  idx: device int32[rank_offsets[p]],
@@ -141,8 +147,9 @@ int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void* stream);
  *                         step mod 2^32, 2)) are zero; the r-th flagged slot of j
  *                         swaps with the r-th flagged slot of its hypercube
  *                         partner, r < min of the two counts.  `batch` ignored.
- * The context grows its scratch to the index count on first use (this may
- * allocate and therefore synchronise the device). */
+ * The context grows its scratch (one word per index plus per-tile counts) on first
+ * use and keeps a device copy of rank_offsets; either may allocate or copy and
+ * therefore synchronise the device on the first call or when the offsets change. */
 int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
                const int64_t* rank_offsets, int32_t batch, void* stream);
 
