@@ -181,7 +181,7 @@ int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream);
  *   0 = threads per workgroup (64, 128 or 256; default 64),
  *   1 = 16-byte chunks per thread per tile (1, 2, 4, 8; default 1),
  *   2 = cap on resident workgroups per CU, enforced by reserving LDS
- *       (0 = no cap, 3..64; default 10: few waves in flight keep the DRAM
+ *       (0 = no cap, 3..64; default 7: few waves in flight keep the DRAM
  *       row-buffer working set small, which is what the streaming kernels want),
  *   3 = non-temporal loads/stores (0/1; default 1),
  *   4 = dissemination: hops per launch when a long partner cycle is walked in

@@ -101,7 +101,7 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
   ctx->scratch_cap = 0;
   ctx->d_offsets = nullptr;
   ctx->h_offsets_pinned = nullptr;
-  ctx->tune = gg_tuning{64, 1, 10, 1, 8};
+  ctx->tune = gg_tuning{64, 1, 7, 1, 8};
   ctx->d_carry = nullptr;
   ctx->carry_cap = 0;
 

@@ -512,7 +512,7 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
   }
   const bool nt = ctx->tune.nontemporal != 0;
   const int64_t edge = (body_lo - e_lo) + (e_hi - body_hi);
-  const int loads = kind == KIND_SGD ? 3 : 6;
+  const int loads = kind == KIND_SGD ? 3 : (kind == KIND_CYCLE ? 5 : 6);  // the cycle walk likes one wave more
 
   // Long dissemination cycles are walked in groups of hops, last group first.
   const int32_t hop_group = ctx->tune.hop_group;
