@@ -42,5 +42,25 @@ def build_library(verbose=False):
     return LIB_PATH
 
 
+C_DRIVER_SRC = os.path.join(ROOT, "tests", "c_abi", "driver.c")
+C_DRIVER_BIN = os.path.join(ROOT, "tests", "c_abi", "driver")
+
+
+def build_c_driver(verbose=False):
+    """Compile the plain-C caller of the ABI (tests/c_abi/driver.c) with gcc against libgg.so."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), C_DRIVER_SRC, "-o", C_DRIVER_BIN, "-L", HERE, "-lgg",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath,$ORIGIN/../../paper_1803_05880_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("gcc failed with exit code %d" % res.returncode)
+    return C_DRIVER_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_driver(verbose=True))
