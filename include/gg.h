@@ -85,6 +85,11 @@ typedef struct {
  * start-up) and uploads them.  *out is written only on success.  Host pointers. */
 int gg_init(const gg_config* cfg, gg_ctx** out);
 
+/* Change the learning rate and momentum used by later calls (the paper's runs
+ * lower the learning rate on a schedule, Sec. 7.3).  Takes effect for calls
+ * enqueued after it returns; NaN is rejected. */
+int gg_set_hyper(gg_ctx* ctx, float lr, float momentum);
+
 /* Free the context's tables and scratch (waits for the device first). */
 int gg_destroy(gg_ctx* ctx);
 

@@ -66,6 +66,7 @@ def lib():
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         L.gg_init.argtypes = [ctypes.POINTER(GGConfig), ctypes.POINTER(vp)]
         L.gg_destroy.argtypes = [vp]
+        L.gg_set_hyper.argtypes = [vp, ctypes.c_float, ctypes.c_float]
         L.gg_partner.argtypes = [vp, i64, vp, vp]
         L.gg_gossip_step.argtypes = [vp, i64, vp, vp, vp, vp, vp, i32, vp]
         L.gg_sgd_step.argtypes = [vp, vp, vp, vp, vp]
@@ -78,7 +79,7 @@ def lib():
         L.gg_set_tuning.argtypes = [vp, i32, i32]
         L.gg_strerror.argtypes = [ctypes.c_int]
         L.gg_strerror.restype = ctypes.c_char_p
-        for name in ("gg_init", "gg_destroy", "gg_partner", "gg_gossip_step", "gg_sgd_step",
+        for name in ("gg_init", "gg_destroy", "gg_set_hyper", "gg_partner", "gg_gossip_step", "gg_sgd_step",
                      "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_shuffle_payload", "gg_copy_probe",
                      "gg_busy_probe", "gg_set_tuning"):
             getattr(L, name).restype = ctypes.c_int
@@ -135,6 +136,9 @@ class Context:
 
     def __exit__(self, *exc):
         self.close()
+
+    def set_hyper(self, lr, momentum):
+        _check(lib().gg_set_hyper(self._h, lr, momentum), "gg_set_hyper")
 
     def partner(self, step):
         """gg_partner: (send_to, recv_from) as int32 numpy arrays."""

@@ -153,6 +153,13 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
   return GG_OK;
 }
 
+extern "C" int gg_set_hyper(gg_ctx* ctx, float lr, float momentum) {
+  if (!ctx || !(lr == lr) || !(momentum == momentum)) return GG_ERR_ARG;
+  ctx->cfg.lr = lr;
+  ctx->cfg.momentum = momentum;
+  return GG_OK;
+}
+
 extern "C" int gg_destroy(gg_ctx* ctx) {
   if (!ctx) return GG_ERR_ARG;
   int rc = GG_OK;

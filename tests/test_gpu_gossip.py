@@ -270,3 +270,22 @@ def test_resume_with_a_fresh_context_continues_bit_exactly():
     half_w, half_m = _run_gpu(W, G, M, n, n, p, 21, 3)
     res_w, res_m = _run_gpu(half_w, G, half_m, n, n, p, 21, 4, first_step=3)
     assert torch.equal(res_w, full_w) and torch.equal(res_m, full_m)
+
+
+def test_learning_rate_schedule_through_set_hyper():
+    # lr drops by 10x after two steps (the paper's step schedule in miniature)
+    p, n = 4, 100_000
+    W, G, M = host_state(p, n, n, seed=22)
+    ctx = gg.Context(p=p, n=n, rank_stride=n, seed=22, lr=0.1, momentum=0.9)
+    w, g, m = W.to(DEV), G.to(DEV), M.to(DEV)
+    Wo, Go, Mo = W.numpy().copy(), G.numpy().copy(), M.numpy().copy()
+    for t in range(5):
+        lr = 0.1 if t < 2 else 0.01
+        ctx.set_hyper(lr, 0.9)
+        ctx.gossip_step(t, w, g, m)
+        og.gossip_step(Wo, Go, Mo, sc.partners(p, 22, p, 0, t)[1], lr, 0.9)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy(), Wo) and np.array_equal(m.cpu().numpy(), Mo)
+    with pytest.raises(gg.GGError):
+        ctx.set_hyper(float("nan"), 0.9)
+    ctx.close()
