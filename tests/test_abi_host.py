@@ -174,3 +174,8 @@ def test_partner_matches_oracle_on_random_configurations():
         assert send.tolist() == o_send and recv.tolist() == o_recv
 
     check()
+
+
+def test_aligned_stride_helper():
+    assert gg.aligned_stride(25_557_032) == 25_557_056 and gg.aligned_stride(64) == 64 and gg.aligned_stride(1) == 64
+    assert gg.aligned_stride(25_557_032, 1024) == 25_558_016
