@@ -353,6 +353,18 @@ def main():
         extras["copy_kernel_GBps"] = round(2.0 * 4 * p * stride / (cp_ms * 1e-3) / 1e9, 1)
         extras["gossip_pct_of_copy_kernel"] = round(100.0 * achieved / extras["copy_kernel_GBps"], 1)
 
+        # the runtime's own device-to-device copy of the same buffer, for reference
+        def rt_copy(t, pairs):
+            a, b = ev(), ev()
+            a.record(stream)
+            scratch.copy_(W)
+            b.record(stream)
+            if pairs is not None:
+                pairs.append((a, b))
+        _, pr = time_loop(torch, rt_copy, reps, 2)
+        rt_ms = sum(event_ms(pr)) / len(pr)
+        extras["runtime_d2d_copy_GBps"] = round(2.0 * 4 * p * stride / (rt_ms * 1e-3) / 1e9, 1)
+
         # staleness-1 variant with a double buffer (scratch doubles as the second w)
         ctx_s = gg.Context(p=p, n=n, rank_stride=stride, seed=0, lr=lr, momentum=mu, staleness=1)
         bufs = [W, scratch]
