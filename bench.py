@@ -382,6 +382,28 @@ def main():
                                               "GBps": round(algo_bytes / (st_ms * 1e-3) / 1e9, 1)}
         ctx_s.close()
 
+        # dissemination topology (the paper's preferred one, Sec. 4.4.2): one step per phase k
+        ctx_d = gg.Context(p=p, n=n, rank_stride=stride, seed=0, lr=lr, momentum=mu, topology=gg.TOPO_DISSEMINATION)
+        L_d = max(1, (p - 1).bit_length())
+        ctx_d.gossip_step(0, W, G, M)                    # first use allocates the carry column
+        torch.cuda.synchronize()
+        per_phase = []
+        for k in range(L_d):
+            def dis(t, pairs, k=k):
+                a, b = ev(), ev()
+                a.record(stream)
+                ctx_d.gossip_step(k + L_d * t, W, G, M)
+                b.record(stream)
+                if pairs is not None:
+                    pairs.append((a, b))
+            _, pr = time_loop(torch, dis, 4, 1)
+            per_phase.append(sum(event_ms(pr)) / len(pr))
+        ctx_d.close()
+        extras["dissemination"] = {
+            "ms_per_phase": [round(x, 4) for x in per_phase],
+            "GBps_mean": round(algo_bytes * len(per_phase) / (sum(per_phase) * 1e-3) / 1e9, 1),
+        }
+
         # layer-wise exchange overlapped with a stand-in compute kernel
         extras["layerwise_overlap"] = layerwise_overlap(torch, gg, gg_synth, ctx, W, G, M, n, k_avg)
 

@@ -43,6 +43,7 @@ def test_config4_scale_out_shape_sampled_windows(staleness):
     cols = _columns(n, 256)
     cd = torch.as_tensor(cols, device=DEV)
     Wo, Go, Mo = _take(W, cd), _take(G, cd), _take(M, cd)
+    W0o, M0o = Wo.copy(), Mo.copy()
     ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=seed, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM,
                      staleness=staleness)
     W2 = torch.empty_like(W) if staleness else None
@@ -58,6 +59,15 @@ def test_config4_scale_out_shape_sampled_windows(staleness):
         og.gossip_step(Wo, Go, Mo, c, gg_synth.LR, gg_synth.MOMENTUM, W_stale=Wo.copy() if staleness else None)
     torch.cuda.synchronize()
     Wfinal = bufs[steps & 1] if staleness else W
+    if not staleness:
+        # reported, not gated at 1e-6: drift of the fp32 path from a float64 run of the same steps
+        W64, G64, M64 = (a.astype(np.float64) for a in (W0o, Go, M0o))
+        for t in range(steps):
+            og.gossip_step(W64, G64, M64, sc.partners(p, seed, p, sc.HYPERCUBE, t)[1], np.float32(gg_synth.LR),
+                           np.float32(gg_synth.MOMENTUM))
+        drift = np.abs(Wo - W64).max() / np.abs(W64).max()
+        print("fp32 vs float64 after %d steps: max |dW| / max |W| = %.3g" % (steps, drift))
+        assert drift < steps * 4 * 2.0 ** -24
     dw = assert_close_fp32(_take(Wfinal, cd), Wo, "W")
     dm = assert_close_fp32(_take(M, cd), Mo, "M")
     assert dw == 0 and dm == 0
