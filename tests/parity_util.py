@@ -7,7 +7,6 @@ same fp32 operations in the same order with no fused multiply-add, so the
 number of elements that differ in any bit is also reported and expected to be 0.
 """
 import numpy as np
-import torch
 
 import gg_synth
 from oracle import gossip as og

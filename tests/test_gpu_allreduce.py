@@ -4,7 +4,6 @@ import numpy as np
 import pytest
 import torch
 
-import gg_synth
 import paper_1803_05880_amd as gg
 from oracle import gossip as og
 from parity_util import assert_close_fp32, host_state

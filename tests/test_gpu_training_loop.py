@@ -6,7 +6,6 @@ are the library's.  Checks the behaviour the paper argues for (Sec. 4.1, 4.5, 6)
 without communication the replicas stay apart, with gossip + partner rotation
 they agree on one model that is as good as the all-reduce baseline's, and the
 ring rotation shows every rank every sample."""
-import numpy as np
 import pytest
 import torch
 

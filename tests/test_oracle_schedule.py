@@ -1,6 +1,5 @@
 """Pins for partner selection and rotation (Sec. 4.3, 4.4, 4.5.1)."""
 import itertools
-import math
 
 import pytest
 
