@@ -29,8 +29,9 @@
  *     j * rank_stride, its n parameters are contiguous, rank_stride >= n.
  *     Buffers whose base address and rank_stride*4 are multiples of 16 bytes take
  *     the vector path; anything 4-byte aligned is accepted.  For full bandwidth make
- *     base addresses and rank_stride*4 multiples of 256 bytes (rank_stride a multiple
- *     of 64): rows that start inside a 128-byte line cost about 13 %.
+ *     base addresses and rank_stride*4 multiples of 4096 bytes (rank_stride a
+ *     multiple of 1024): measured on p = 64 ResNet50-sized rows, rows aligned to
+ *     32 / 64 / 128 / 4096 bytes run at 5.4 / 6.0 / 6.4 / 6.57 TB/s.
  *   - fp32 arithmetic, every multiply/add/subtract rounded on its own (no fused
  *     multiply-add), denormals kept.
  */

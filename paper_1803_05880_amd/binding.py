@@ -24,8 +24,8 @@ MAX_RANKS = 1024
 TUNE_THREADS, TUNE_CHUNKS, TUNE_BLOCKS_PER_CU, TUNE_NONTEMPORAL, TUNE_HOP_GROUP = 0, 1, 2, 3, 4
 
 
-def aligned_stride(n, elements=64):
-    """Smallest rank_stride >= n whose rows start on 256-byte boundaries (the layout
+def aligned_stride(n, elements=1024):
+    """Smallest rank_stride >= n whose rows start on 4096-byte boundaries (the layout
     the kernels reach full bandwidth with; see include/gg.h)."""
     return (int(n) + elements - 1) // elements * elements
 

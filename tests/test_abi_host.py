@@ -177,5 +177,5 @@ def test_partner_matches_oracle_on_random_configurations():
 
 
 def test_aligned_stride_helper():
-    assert gg.aligned_stride(25_557_032) == 25_557_056 and gg.aligned_stride(64) == 64 and gg.aligned_stride(1) == 64
-    assert gg.aligned_stride(25_557_032, 1024) == 25_558_016
+    assert gg.aligned_stride(25_557_032) == 25_558_016 and gg.aligned_stride(1024) == 1024 and gg.aligned_stride(1) == 1024
+    assert gg.aligned_stride(25_557_032, 64) == 25_557_056
