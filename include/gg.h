@@ -31,7 +31,7 @@
  *     the vector path; anything 4-byte aligned is accepted.  For full bandwidth make
  *     base addresses and rank_stride*4 multiples of 4096 bytes (rank_stride a
  *     multiple of 1024): measured on p = 64 ResNet50-sized rows, rows aligned to
- *     32 / 64 / 128 / 4096 bytes run at 5.4 / 6.0 / 6.4 / 6.57 TB/s.
+ *     32 / 64 / 128 / 4096 bytes run at 6.1 / 6.4 / 6.5 / 6.57 TB/s.
  *   - fp32 arithmetic, every multiply/add/subtract rounded on its own (no fused
  *     multiply-add), denormals kept.
  */

@@ -37,7 +37,7 @@ struct step_args {
 // here live for a microsecond or two and a dependent table lookup in global
 // memory would be a visible part of that.
 struct pair_table {
-  uint32_t jc[GG_MAX_RANKS / 2];  // j | c << 16
+  uint32_t jc[GG_MAX_RANKS / 2];  // j | c << 10 | tile shift << 20 (lean kernel only)
 };
 
 // Streaming 16-byte store with the write-through scope bits set next to the
@@ -107,8 +107,8 @@ __device__ __forceinline__ void pair_tile(const step_args& a, int64_t x0, const 
 template <typename V, int MODE, int U, bool NT>
 __global__ void __launch_bounds__(256) gossip_pair_kernel(step_args a, pair_table pt) {
   const uint32_t jc = pt.jc[blockIdx.y];
-  const int64_t j = jc & 0xffffu;
-  const int64_t c = jc >> 16;
+  const int64_t j = jc & 0x3ffu;
+  const int64_t c = (jc >> 10) & 0x3ffu;
   const V* wj = reinterpret_cast<const V*>(a.w + j * a.stride);
   const V* wc = reinterpret_cast<const V*>(a.w + c * a.stride);
   const V* gj = reinterpret_cast<const V*>(a.g + j * a.stride);
@@ -136,10 +136,12 @@ __global__ void __launch_bounds__(256) gossip_pair_kernel(step_args a, pair_tabl
 template <int MODE, bool NT>
 __global__ void __launch_bounds__(64) gossip_pair_lean_kernel(step_args a, pair_table pt) {
   const uint32_t jc = pt.jc[blockIdx.y];
-  const int64_t j = jc & 0xffffu;
-  const int64_t c = jc >> 16;
-  const int64_t i = a.rng.lo + (int64_t)blockIdx.x * 64 + threadIdx.x;
-  if (i >= a.rng.lo + a.rng.count) return;
+  const int64_t j = jc & 0x3ffu;
+  const int64_t c = (jc >> 10) & 0x3ffu;
+  // Tiles are laid so that rank j's 1 KB wavefront accesses start on 1 KB boundaries even
+  // when the rows themselves do not (the host passes the shift, 0 for aligned layouts).
+  const int64_t i = a.rng.lo + (int64_t)blockIdx.x * 64 + threadIdx.x - (int64_t)(jc >> 20);
+  if (i < a.rng.lo || i >= a.rng.lo + a.rng.count) return;
   const v4f* wj = reinterpret_cast<const v4f*>(a.w + j * a.stride) + i;
   const v4f* wc = reinterpret_cast<const v4f*>(a.w + c * a.stride) + i;
   const v4f* gj = reinterpret_cast<const v4f*>(a.g + j * a.stride) + i;
@@ -422,9 +424,23 @@ void launch_one(int kind, const launch_ctx& lc, const step_args& a) {
   const gg_grid& gd = lc.gd;
   hipStream_t s = lc.s;
   if (kind == KIND_PAIR) {
-    if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles)
-      hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, *lc.pt);
-    else
+    if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles &&
+        a.tiles < 0x7fffffffLL) {
+      // per-pair tile shift: chunks between the start of the range in rank j's row and the
+      // 1 KB boundary below it; one extra (partial) tile column when any row is off-boundary
+      pair_table pt = *lc.pt;
+      bool shifted = false;
+      for (int32_t q = 0; q < a.p / 2; ++q) {
+        const uint64_t j = pt.jc[q] & 0x3ffu;
+        const uint64_t first = (uint64_t)(uintptr_t)(a.w + j * a.stride) / 16 + (uint64_t)a.rng.lo;
+        const uint32_t sh = (uint32_t)(first % 64);
+        pt.jc[q] |= sh << 20;
+        shifted = shifted || sh != 0;
+      }
+      dim3 grid = gd.grid;
+      if (shifted) grid.x += 1;
+      hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), grid, gd.block, gd.lds_bytes, s, a, pt);
+    } else
       hipLaunchKernelGGL((gossip_pair_kernel<V, MODE, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, *lc.pt);
   }
   else if (kind == KIND_CYCLE)
@@ -494,7 +510,7 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
     const int32_t low = a.shift - 1;
     for (int32_t q = 0; q < p / 2; ++q) {
       const int32_t v0 = ((q & ~low) << 1) | (q & low);
-      pt.jc[q] = (uint32_t)sigma_host[v0] | ((uint32_t)sigma_host[v0 | a.shift] << 16);
+      pt.jc[q] = (uint32_t)sigma_host[v0] | ((uint32_t)sigma_host[v0 | a.shift] << 10);
     }
     for (int32_t q = p / 2; q < GG_MAX_RANKS / 2; ++q) pt.jc[q] = 0;
   }
