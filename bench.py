@@ -138,6 +138,25 @@ def cpu_baseline(p, lr, mu):
     }
 
 
+def make_buckets(seg, n, target):
+    """Group per-layer segments (ascending offsets seg[0..]) into buckets of at least
+    `target` elements in back-propagation order (last layer first).  Returns [lo, hi)
+    element ranges, highest first, that tile [0, n) exactly.  Cuts are moved up to
+    256-byte boundaries: the few elements below a rounded-up cut belong to layers
+    that are ready later, so they simply travel with the next bucket."""
+    up = lambda x: n if x >= n else (int(x) + 63) // 64 * 64
+    buckets, hi = [], len(seg) - 1
+    while hi > 0:
+        lo = hi
+        while lo > 0 and seg[hi] - seg[lo] < target:
+            lo -= 1
+        b = (up(seg[lo]) if lo > 0 else 0, up(seg[hi]))
+        if b[1] > b[0]:
+            buckets.append(b)
+        hi = lo
+    return buckets
+
+
 def layerwise_overlap(torch, gg, gg_synth, ctx, W, G, M, n, gossip_ms, reps=5):
     """Layer-wise exchange overlapped with computation (Sec. 5, 5.1): the buffer is cut
     into 161 per-layer segments, grouped into ~24 buckets in back-propagation order
@@ -146,17 +165,7 @@ def layerwise_overlap(torch, gg, gg_synth, ctx, W, G, M, n, gossip_ms, reps=5):
     "its" piece is done.  Compute is sized 3.5x the exchange, the ratio the paper
     reports (96 ms vs 27 ms).  Returns the three timings and the hidden fraction."""
     seg, _ = gg_synth.segment_layout(n, 161, seed=0)
-    buckets, hi = [], len(seg) - 1
-    target = n // 24
-    while hi > 0:
-        lo = hi
-        while lo > 0 and seg[hi] - seg[lo] < target:
-            lo -= 1
-        # cut at 256-byte boundaries: the few elements below a rounded-up cut belong to
-        # layers that are ready later, so they simply travel with the next bucket
-        up = lambda x: n if x >= n else (int(x) + 63) // 64 * 64
-        buckets.append((up(seg[lo]) if lo > 0 else 0, up(seg[hi])))
-        hi = lo
+    buckets = make_buckets(seg, n, n // 24)
     main = torch.cuda.current_stream()
     side = torch.cuda.Stream()
     sink = torch.zeros(1, device=W.device)
