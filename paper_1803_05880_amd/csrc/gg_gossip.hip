@@ -390,8 +390,10 @@ __global__ void __launch_bounds__(256) sgd_kernel(step_args a) {
 template <bool NT>
 __global__ void __launch_bounds__(64) sgd_lean_kernel(step_args a) {
   const int64_t j = blockIdx.y;
-  const int64_t i = a.rng.lo + (int64_t)blockIdx.x * 64 + threadIdx.x;
-  if (i >= a.rng.lo + a.rng.count) return;
+  // tiles start on 1 KB boundaries of this rank's row even when the row itself does not
+  const int64_t sh = (int64_t)(((uint64_t)(uintptr_t)(a.w + j * a.stride) / 16 + (uint64_t)a.rng.lo) % 64);
+  const int64_t i = a.rng.lo + (int64_t)blockIdx.x * 64 + threadIdx.x - sh;
+  if (i < a.rng.lo || i >= a.rng.lo + a.rng.count) return;
   const v4f* w = reinterpret_cast<const v4f*>(a.w + j * a.stride) + i;
   const v4f* g = reinterpret_cast<const v4f*>(a.g + j * a.stride) + i;
   v4f* m = reinterpret_cast<v4f*>(a.m + j * a.stride) + i;
@@ -450,8 +452,13 @@ void launch_one(int kind, const launch_ctx& lc, const step_args& a) {
     else
       hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, (U > 2 ? 2 : U), NT, false>), gd.grid, gd.block, gd.lds_bytes,
                          s, a, lc.ca);
-  else if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles)
-    hipLaunchKernelGGL((sgd_lean_kernel<NT>), gd.grid, gd.block, gd.lds_bytes, s, a);
+  else if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles &&
+           a.tiles < 0x7fffffffLL) {
+    dim3 grid = gd.grid;
+    const bool aligned = ((uint64_t)(uintptr_t)a.w / 16 + (uint64_t)a.rng.lo) % 64 == 0 && a.stride % 256 == 0;
+    if (!aligned) grid.x += 1;  // shifted tile grids need one more (partial) column
+    hipLaunchKernelGGL((sgd_lean_kernel<NT>), grid, gd.block, gd.lds_bytes, s, a);
+  }
   else
     hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a);
 }
