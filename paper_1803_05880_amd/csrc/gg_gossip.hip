@@ -421,46 +421,71 @@ struct launch_ctx {
   bool split;
 };
 
+// The lean kernels serve the default launch shape: 16-byte accesses, one chunk per
+// thread, one wavefront per workgroup, one tile per workgroup.
+template <typename V, int U>
+bool lean_shape(const gg_grid& gd, const step_args& a) {
+  return sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles &&
+         a.tiles < 0x7fffffffLL;
+}
+
+// First 16-byte chunk of the range in rank j's row, counted from address 0: its
+// remainder mod 64 is how far the row's tiles sit above a 1 KB boundary.
+inline uint64_t first_chunk(const step_args& a, uint64_t j) {
+  return (uint64_t)(uintptr_t)(a.w + j * a.stride) / 16 + (uint64_t)a.rng.lo;
+}
+
+template <typename V, int MODE, int U, bool NT>
+void launch_pair(const launch_ctx& lc, const step_args& a) {
+  const gg_grid& gd = lc.gd;
+  if (!lean_shape<V, U>(gd, a)) {
+    hipLaunchKernelGGL((gossip_pair_kernel<V, MODE, U, NT>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, *lc.pt);
+    return;
+  }
+  // per-pair tile shift; one extra (partial) tile column when any row is off a 1 KB boundary
+  pair_table pt = *lc.pt;
+  bool shifted = false;
+  for (int32_t q = 0; q < a.p / 2; ++q) {
+    const uint32_t sh = (uint32_t)(first_chunk(a, pt.jc[q] & 0x3ffu) % 64);
+    pt.jc[q] |= sh << 20;
+    shifted = shifted || sh != 0;
+  }
+  dim3 grid = gd.grid;
+  if (shifted) grid.x += 1;
+  hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), grid, gd.block, gd.lds_bytes, lc.s, a, pt);
+}
+
+template <typename V, int MODE, int U, bool NT>
+void launch_cycle(const launch_ctx& lc, const step_args& a) {
+  const gg_grid& gd = lc.gd;
+  constexpr int UC = U > 2 ? 2 : U;  // the walk keeps three ranks in registers: two chunks at most
+  if (lc.split)
+    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, true>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca);
+  else
+    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, false>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca);
+}
+
+template <typename V, int U, bool NT>
+void launch_sgd(const launch_ctx& lc, const step_args& a) {
+  const gg_grid& gd = lc.gd;
+  if (!lean_shape<V, U>(gd, a)) {
+    hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, gd.lds_bytes, lc.s, a);
+    return;
+  }
+  dim3 grid = gd.grid;
+  const bool on_boundaries = first_chunk(a, 0) % 64 == 0 && a.stride % 256 == 0;
+  if (!on_boundaries) grid.x += 1;  // shifted tile grids need one more (partial) column
+  hipLaunchKernelGGL((sgd_lean_kernel<NT>), grid, gd.block, gd.lds_bytes, lc.s, a);
+}
+
 template <typename V, int MODE, int U, bool NT>
 void launch_one(int kind, const launch_ctx& lc, const step_args& a) {
-  const gg_grid& gd = lc.gd;
-  hipStream_t s = lc.s;
-  if (kind == KIND_PAIR) {
-    if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles &&
-        a.tiles < 0x7fffffffLL) {
-      // per-pair tile shift: chunks between the start of the range in rank j's row and the
-      // 1 KB boundary below it; one extra (partial) tile column when any row is off-boundary
-      pair_table pt = *lc.pt;
-      bool shifted = false;
-      for (int32_t q = 0; q < a.p / 2; ++q) {
-        const uint64_t j = pt.jc[q] & 0x3ffu;
-        const uint64_t first = (uint64_t)(uintptr_t)(a.w + j * a.stride) / 16 + (uint64_t)a.rng.lo;
-        const uint32_t sh = (uint32_t)(first % 64);
-        pt.jc[q] |= sh << 20;
-        shifted = shifted || sh != 0;
-      }
-      dim3 grid = gd.grid;
-      if (shifted) grid.x += 1;
-      hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), grid, gd.block, gd.lds_bytes, s, a, pt);
-    } else
-      hipLaunchKernelGGL((gossip_pair_kernel<V, MODE, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a, *lc.pt);
-  }
+  if (kind == KIND_PAIR)
+    launch_pair<V, MODE, U, NT>(lc, a);
   else if (kind == KIND_CYCLE)
-    if (lc.split)
-      hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, (U > 2 ? 2 : U), NT, true>), gd.grid, gd.block, gd.lds_bytes, s,
-                         a, lc.ca);
-    else
-      hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, (U > 2 ? 2 : U), NT, false>), gd.grid, gd.block, gd.lds_bytes,
-                         s, a, lc.ca);
-  else if (sizeof(V) == sizeof(v4f) && U == 1 && gd.block.x == 64 && (int64_t)gd.grid.x == a.tiles &&
-           a.tiles < 0x7fffffffLL) {
-    dim3 grid = gd.grid;
-    const bool aligned = ((uint64_t)(uintptr_t)a.w / 16 + (uint64_t)a.rng.lo) % 64 == 0 && a.stride % 256 == 0;
-    if (!aligned) grid.x += 1;  // shifted tile grids need one more (partial) column
-    hipLaunchKernelGGL((sgd_lean_kernel<NT>), grid, gd.block, gd.lds_bytes, s, a);
-  }
+    launch_cycle<V, MODE, U, NT>(lc, a);
   else
-    hipLaunchKernelGGL((sgd_kernel<V, U, NT>), gd.grid, gd.block, gd.lds_bytes, s, a);
+    launch_sgd<V, U, NT>(lc, a);
 }
 
 template <typename V, int MODE>
