@@ -185,7 +185,16 @@ __global__ void __launch_bounds__(64) gossip_pair_lean_kernel(step_args a, pair_
 // ranks into gcd(p, 2^k) cycles v0, v0+2^k, v0+2*2^k, ...; grid row = cycle.  One
 // thread walks its cycle for one chunk and carries the previous rank's
 // contribution in registers, so each rank's w, g, m are read once and written
-// once, in place.  The communicator row sits in LDS (read at every hop).
+// once, in place.
+//
+// Communicator row (virtual -> world rank) for the cycle walk, two ranks per word,
+// passed by value like pair_table: a hop's rank comes from one scalar load in the
+// kernel-argument segment instead of an LDS copy that every short-lived workgroup
+// would first have to fill behind a barrier.
+struct rank_table {
+  uint32_t r2[GG_MAX_RANKS / 2];
+};
+
 // A long cycle keeps 5 address streams open per rank on it, and bandwidth falls
 // with the number of streams touched at once.  SPLIT cuts the walk into groups
 // of consecutive hops, one launch per group, LAST group first: a group's
@@ -199,13 +208,13 @@ struct cycle_args {
 };
 
 template <typename V, int MODE, int U, bool NT, bool SPLIT>
-__global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_args ca) {
-  __shared__ uint16_t s_sigma[GG_MAX_RANKS];
-  for (int32_t i = threadIdx.x; i < a.p; i += blockDim.x) s_sigma[i] = a.sigma[i];
-  __syncthreads();
+__global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_args ca, rank_table rt) {
   const int32_t v0 = blockIdx.y;
   // world rank at hop t of this cycle: virtual rank (v0 + t*shift) mod p
-  auto rank_at = [&](int32_t t) -> int64_t { return s_sigma[(v0 + t * a.shift) % a.p]; };
+  auto rank_at = [&](int32_t t) -> int64_t {
+    const uint32_t v = (uint32_t)((v0 + t * a.shift) % a.p);
+    return (rt.r2[v >> 1] >> ((v & 1u) * 16u)) & 0xffffu;
+  };
   const int64_t per_tile = (int64_t)blockDim.x * U;
   for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
     int64_t idx[U];
@@ -417,6 +426,7 @@ struct launch_ctx {
   gg_grid gd;
   hipStream_t s;
   const pair_table* pt;
+  const rank_table* rt;
   cycle_args ca;
   bool split;
 };
@@ -460,9 +470,11 @@ void launch_cycle(const launch_ctx& lc, const step_args& a) {
   const gg_grid& gd = lc.gd;
   constexpr int UC = U > 2 ? 2 : U;  // the walk keeps three ranks in registers: two chunks at most
   if (lc.split)
-    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, true>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca);
+    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, true>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca,
+                       *lc.rt);
   else
-    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, false>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca);
+    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, false>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca,
+                       *lc.rt);
 }
 
 template <typename V, int U, bool NT>
@@ -546,9 +558,14 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
     }
     for (int32_t q = p / 2; q < GG_MAX_RANKS / 2; ++q) pt.jc[q] = 0;
   }
+  rank_table rt;
   if (kind == KIND_CYCLE) {
     rows = gcd32(p, a.shift);
     cycle_len = p / (int32_t)rows;
+    for (int32_t v = 0; v < GG_MAX_RANKS; v += 2) {
+      const uint32_t r0 = v < p ? sigma_host[v] : 0u, r1 = v + 1 < p ? sigma_host[v + 1] : 0u;
+      rt.r2[v >> 1] = r0 | (r1 << 16);
+    }
   }
   const bool vec_ok = gg_aligned(a.w, 16) && gg_aligned(a.g, 16) && gg_aligned(a.m, 16) &&
                       gg_aligned(a.wn, 16) && (a.stride % 4 == 0);
@@ -592,14 +609,14 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
       int U = ctx->tune.chunks;
       if (kind == KIND_CYCLE && U > 2) U = 2;
       a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
-      launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, loads), s, &pt, ca, split};
+      launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, loads), s, &pt, &rt, ca, split};
       a.tiles = lc.gd.tiles;
       launch_any<v4f>(kind, mode, U, nt, lc, a);
       GG_HIP_TRY(hipGetLastError());
     }
     if (edge > 0) {
       a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
-      launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, loads), s, &pt, ca, split};
+      launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, loads), s, &pt, &rt, ca, split};
       a.tiles = lc.gd.tiles;
       launch_any<float>(kind, mode, 1, nt, lc, a);
       GG_HIP_TRY(hipGetLastError());
