@@ -22,7 +22,6 @@ struct step_args {
   const float* g;
   float* m;
   float* wn;              // where new weights go (== w when in place)
-  const uint16_t* sigma;  // device row of the current communicator: virtual -> world rank
   int64_t stride;         // elements between consecutive ranks
   gg_range rng;           // work items, in units of the access type V
   int64_t tiles;          // tiles per grid row
@@ -660,7 +659,6 @@ extern "C" int gg_gossip_step(gg_ctx* ctx, int64_t step, float* w, const float* 
   a.g = g;
   a.m = m;
   a.wn = w_next ? w_next : w;
-  a.sigma = ctx->d_sigma + (size_t)r * cfg.p;
   a.stride = cfg.rank_stride;
   a.shift = int32_t(1) << k;
   a.p = cfg.p;
@@ -694,7 +692,6 @@ extern "C" int gg_sgd_step(gg_ctx* ctx, float* w, const float* g, float* m, void
   a.g = g;
   a.m = m;
   a.wn = w;
-  a.sigma = ctx->d_sigma;
   a.stride = ctx->cfg.rank_stride;
   a.shift = 1;
   a.p = ctx->cfg.p;
