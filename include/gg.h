@@ -25,6 +25,10 @@
  *     the default stream) and the call returns without waiting.
  *   - The library keeps no step counter: `step` is an argument, so any step can
  *     be replayed.
+ *   - A context is not thread-safe: call it from one host thread at a time.  Calls
+ *     may target different streams; work that shares the context's scratch
+ *     (two gg_shuffle calls, two split dissemination steps) must be ordered by the
+ *     caller.
  *   - All [p][.] buffers share one layout: rank j starts at element
  *     j * rank_stride, its n parameters are contiguous, rank_stride >= n.
  *     Buffers whose base address and rank_stride*4 are multiples of 16 bytes take
