@@ -289,3 +289,19 @@ def test_learning_rate_schedule_through_set_hyper():
     with pytest.raises(gg.GGError):
         ctx.set_hyper(float("nan"), 0.9)
     ctx.close()
+
+
+def test_infinities_and_nans_propagate_like_the_oracle():
+    p, n = 2, 64
+    W = torch.zeros(p, n); G = torch.zeros(p, n); M = torch.zeros(p, n)
+    W[0, :6] = torch.tensor([float("inf"), float("-inf"), float("inf"), float("nan"), 1.0, 3e38])
+    W[1, :6] = torch.tensor([1.0, 2.0, float("-inf"), 5.0, float("nan"), 3e38])
+    G[0, 6] = float("inf"); M[1, 7] = float("nan")
+    wg, mg = _run_gpu(W, G, M, n, n, p, 0, 1)
+    with np.errstate(all="ignore"):
+        Wo, Mo = oracle_run(W, G, M, n, p, 0, 1)
+    for got, exp in ((wg.numpy(), Wo), (mg.numpy(), Mo)):
+        assert np.array_equal(np.isnan(got), np.isnan(exp))
+        ok = ~np.isnan(exp)
+        assert np.array_equal(got[ok], exp[ok])          # infinities and finite values bit for bit
+    assert np.isnan(Wo).sum() >= 4 and np.isinf(Wo).sum() >= 2
