@@ -22,6 +22,7 @@ AVG_MODEL, AVG_GRAD, AVG_NONE = 0, 1, 2
 SHUF_PARTNER_SWAP, SHUF_RING = 0, 1
 MAX_RANKS = 1024
 TUNE_THREADS, TUNE_CHUNKS, TUNE_BLOCKS_PER_CU, TUNE_NONTEMPORAL, TUNE_HOP_GROUP = 0, 1, 2, 3, 4
+TUNE_WALK_TILES, TUNE_WALK_AHEAD, TUNE_WALK_STRIDED = 5, 6, 7
 
 
 def aligned_stride(n, elements=1024):

@@ -101,7 +101,7 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
   ctx->scratch_cap = 0;
   ctx->d_offsets = nullptr;
   ctx->h_offsets_pinned = nullptr;
-  ctx->tune = gg_tuning{64, 1, 7, 1, 8};
+  ctx->tune = gg_tuning{64, 1, 7, 1, 8, 0, 1, 0, 0, 1, 0, 0, 1, 1, 0};
   ctx->d_carry = nullptr;
   ctx->carry_cap = 0;
 
@@ -222,6 +222,48 @@ extern "C" int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value) {
     case 4:
       if (value < 0 || value == 1 || value > GG_MAX_RANKS) return GG_ERR_ARG;
       ctx->tune.hop_group = value;
+      return GG_OK;
+    case 13:
+      if (value != 1 && value != 2 && value != 4 && value != 8) return GG_ERR_ARG;
+      ctx->tune.walk_wg_waves = value;
+      return GG_OK;
+    case 14:
+      if (value != 0 && value != 1) return GG_ERR_ARG;
+      ctx->tune.walk_barrier = value;
+      return GG_OK;
+    case 5:
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return GG_ERR_ARG;
+      ctx->tune.walk_tiles = value;
+      return GG_OK;
+    case 6:
+      if (value != 0 && value != 1) return GG_ERR_ARG;
+      ctx->tune.walk_ahead = value;
+      return GG_OK;
+    case 7:
+      if (value < 0 || value > 65536) return GG_ERR_ARG;
+      ctx->tune.walk_strided = value;
+      return GG_OK;
+    case 8:
+      if (value < 0 || value > 64) return GG_ERR_ARG;
+      ctx->tune.walk_waves = value;
+      return GG_OK;
+    case 9:
+      if (value < 0 || value > 4096 || (value & (value - 1))) return GG_ERR_ARG;
+      ctx->tune.rows_step = value;
+      return GG_OK;
+    case 10:
+      if (value != 1 && value != 2 && value != 4 && value != 8) return GG_ERR_ARG;
+      if (value * ctx->tune.rows_chunks > 8) return GG_ERR_ARG;
+      ctx->tune.rows_waves = value;
+      return GG_OK;
+    case 11:
+      if (value != 1 && value != 2 && value != 4 && value != 8) return GG_ERR_ARG;
+      if (value * ctx->tune.rows_waves > 8) return GG_ERR_ARG;
+      ctx->tune.rows_chunks = value;
+      return GG_OK;
+    case 12:
+      if (value != 0 && (value < 3 || value > 64)) return GG_ERR_ARG;
+      ctx->tune.rows_wg_per_cu = value;
       return GG_OK;
     default:
       return GG_ERR_ARG;

@@ -42,8 +42,11 @@ struct pair_table {
 // Streaming 16-byte store with the write-through scope bits set next to the
 // non-temporal hint: measured about 1 % faster than the hint alone for this
 // read-modify-write stream (the line just read is never needed again on chip).
+// A store of more than 8 bytes reads its data registers after it has issued; a
+// vector ALU instruction that overwrites them needs two wait states in between.
+// The compiler pads its own stores but cannot see into this one, hence the s_nop.
 __device__ __forceinline__ void st_stream(v4f* ptr, v4f val) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(ptr), "v"(val) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(ptr), "v"(val) : "memory");
 }
 
 // v = mu*m + lr*g ; returns T = w - v.  Three roundings for v, one for T.
@@ -176,6 +179,72 @@ __global__ void __launch_bounds__(64) gossip_pair_lean_kernel(step_args a, pair_
     gg_st<false>(nc, outc);
     gg_st<false>(mj, vj);
     gg_st<false>(mc, vc);
+  }
+}
+
+// Row-aware form of the lean kernel.  Device memory interleaves consecutive 128-byte
+// pieces over its channels, so addresses 32 KB apart fall into the same channel and, eight
+// of them, into one DRAM row.  A workgroup therefore takes tiles that are `1 << log2_step`
+// tiles (32 KB by default) apart -- wavefront w, chunk u handles tile
+//   (blockIdx.x >> log2_step) * (step * W * U) + (blockIdx.x & (step - 1)) + (w * U + u) * step
+// -- and touches each row it opens W * U times at once instead of once, while consecutive
+// workgroups still take consecutive tiles.
+template <int MODE, int U>
+__global__ void __launch_bounds__(512 / U) gossip_pair_rows_kernel(step_args a, pair_table pt, int32_t log2_step) {
+  const uint32_t jc = pt.jc[blockIdx.y];
+  const int64_t j = jc & 0x3ffu;
+  const int64_t c = (jc >> 10) & 0x3ffu;
+  const int64_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t W = blockDim.x >> 6;
+  const int64_t bx = blockIdx.x;
+  const int64_t tile0 = (((bx >> log2_step) * W * U + wave * U) << log2_step) + (bx & ((int64_t(1) << log2_step) - 1));
+  const v4f* wj = reinterpret_cast<const v4f*>(a.w + j * a.stride);
+  const v4f* wc = reinterpret_cast<const v4f*>(a.w + c * a.stride);
+  const v4f* gj = reinterpret_cast<const v4f*>(a.g + j * a.stride);
+  const v4f* gc = reinterpret_cast<const v4f*>(a.g + c * a.stride);
+  v4f* mj = reinterpret_cast<v4f*>(a.m + j * a.stride);
+  v4f* mc = reinterpret_cast<v4f*>(a.m + c * a.stride);
+  v4f* nj = reinterpret_cast<v4f*>(a.wn + j * a.stride);
+  v4f* nc = reinterpret_cast<v4f*>(a.wn + c * a.stride);
+  int64_t i[U];
+  bool on[U];
+  v4f Wj[U], Wc[U], Gj[U], Gc[U], Mj[U], Mc[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    i[u] = a.rng.lo + ((tile0 + ((int64_t)u << log2_step)) << 6) + lane - (int64_t)(jc >> 20);
+    on[u] = i[u] >= a.rng.lo && i[u] < a.rng.lo + a.rng.count;
+    if (on[u]) {
+      Wj[u] = gg_ld<true>(wj + i[u]);
+      Wc[u] = gg_ld<true>(wc + i[u]);
+      Gj[u] = gg_ld<true>(gj + i[u]);
+      Gc[u] = gg_ld<true>(gc + i[u]);
+      Mj[u] = gg_ld<true>(mj + i[u]);
+      Mc[u] = gg_ld<true>(mc + i[u]);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (!on[u]) continue;
+    v4f vj, vc, outj, outc;
+    if (MODE == MODE_GRAD) {
+      const v4f gbar = (Gj[u] + Gc[u]) * 0.5f;
+      outj = local_update(Wj[u], gbar, Mj[u], a.lr, a.mu, vj);
+      outc = local_update(Wc[u], gbar, Mc[u], a.lr, a.mu, vc);
+    } else {
+      const v4f Tj = local_update(Wj[u], Gj[u], Mj[u], a.lr, a.mu, vj);
+      const v4f Tc = local_update(Wc[u], Gc[u], Mc[u], a.lr, a.mu, vc);
+      if (MODE == MODE_SYNC) {
+        outj = (Tj + Tc) * 0.5f;
+        outc = outj;
+      } else {
+        outj = (Tj + Wc[u]) * 0.5f;
+        outc = (Tc + Wj[u]) * 0.5f;
+      }
+    }
+    st_stream(nj + i[u], outj);
+    st_stream(nc + i[u], outc);
+    st_stream(mj + i[u], vj);
+    st_stream(mc + i[u], vc);
   }
 }
 
@@ -350,6 +419,138 @@ __global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_ar
   }
 }
 
+// The same walk with the whole chip in step.  One wavefront owns U tiles and walks the
+// cycle once for all of them, so a launch needs only about as many wavefronts as the chip
+// holds at a time: they start together and advance hop by hop at the pace of the memory
+// system, and at any moment only the rows of two or three ranks are being streamed --
+// however long the cycle.  (With one tile per wavefront the walks start one after another
+// and every rank of the cycle is open somewhere on the chip at the same time, which costs
+// DRAM row-buffer and translation locality.)  Each rank is read once and written once, in
+// place, in one launch: no carry column, no re-reads.
+//   tile(u) = (blockIdx.x / tile_step) * tile_mul + blockIdx.x % tile_step + u * tile_step
+struct walk_args {
+  int32_t cycle_len;
+  int32_t hop_barrier;
+  int64_t tile_mul, tile_step;
+};
+
+template <int MODE, int U, bool AHEAD>
+__global__ void __launch_bounds__(U >= 8 ? 64 : 512 / U) gossip_cycle_walk_kernel(step_args a, walk_args wa, rank_table rt) {
+  const int32_t v0 = blockIdx.y;
+  auto rank_at = [&](int32_t t) -> int64_t {
+    const uint32_t v = (uint32_t)((v0 + t * a.shift) % a.p);
+    return (rt.r2[v >> 1] >> ((v & 1u) * 16u)) & 0xffffu;
+  };
+  int64_t idx[U];
+  bool on[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int64_t bx = blockIdx.x;
+    const int64_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t x = ((bx / wa.tile_step) * wa.tile_mul + bx % wa.tile_step + (wave * U + u) * wa.tile_step) * 64 + lane;
+    on[u] = x < a.rng.count;
+    idx[u] = a.rng.lo + x;
+  }
+  auto load = [&](int64_t rank, v4f* w, v4f* g, v4f* m) {
+    const v4f* pw = reinterpret_cast<const v4f*>(a.w + rank * a.stride);
+    const v4f* pg = reinterpret_cast<const v4f*>(a.g + rank * a.stride);
+    const v4f* pm = reinterpret_cast<const v4f*>(a.m + rank * a.stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (on[u]) {
+        w[u] = gg_ld<true>(pw + idx[u]);
+        g[u] = gg_ld<true>(pg + idx[u]);
+        m[u] = gg_ld<true>(pm + idx[u]);
+      }
+  };
+  auto store_one = [&](float* base, int64_t row, const v4f* val) {
+    v4f* ptr = reinterpret_cast<v4f*>(base + row * a.stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (on[u]) st_stream(ptr + idx[u], val[u]);
+  };
+
+  // first rank of the cycle: its new weights need the LAST rank's contribution, so what
+  // closes the cycle stays in registers until the walk comes round
+  v4f first[U];   // SYNC/STALE: T of the first rank; GRAD: its gradient
+  v4f fw[U], fm[U];  // GRAD only: the first rank's weights and momentum
+  v4f carry[U];
+  const int64_t rank0 = rank_at(0);
+  {
+    v4f w0[U], g0[U], m0[U], v[U];
+    load(rank0, w0, g0, m0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (MODE == MODE_GRAD) {
+        first[u] = g0[u];
+        fw[u] = w0[u];
+        fm[u] = m0[u];
+        carry[u] = g0[u];
+      } else {
+        first[u] = local_update(w0[u], g0[u], m0[u], a.lr, a.mu, v[u]);
+        carry[u] = (MODE == MODE_SYNC) ? first[u] : w0[u];
+      }
+    }
+    if (MODE != MODE_GRAD) store_one(a.m, rank0, v);
+  }
+
+  // finish one rank from its loaded w, g, m and the carry of the rank before it
+  auto finish = [&](int64_t rank, const v4f* cw, const v4f* cg, const v4f* cm) {
+    v4f v[U], out[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (MODE == MODE_GRAD) {
+        const v4f gbar = (cg[u] + carry[u]) * 0.5f;
+        out[u] = local_update(cw[u], gbar, cm[u], a.lr, a.mu, v[u]);
+        carry[u] = cg[u];
+      } else {
+        const v4f T = local_update(cw[u], cg[u], cm[u], a.lr, a.mu, v[u]);
+        out[u] = (T + carry[u]) * 0.5f;
+        carry[u] = (MODE == MODE_SYNC) ? T : cw[u];
+      }
+    }
+    store_one(a.m, rank, v);
+    store_one(a.wn, rank, out);
+    if (wa.hop_barrier) __syncthreads();  // keeps the workgroup's wavefronts on the same rank (uniform trip count)
+  };
+  const int32_t len = wa.cycle_len;
+  if (AHEAD) {
+    // two register sets take turns, so the next rank's loads are in flight while the
+    // current one is finished and no register copies tie the two together
+    v4f aw[U], ag[U], am[U], bw[U], bg[U], bm[U];
+    load(rank_at(1), aw, ag, am);
+    for (int32_t t = 1; t < len; t += 2) {
+      if (t + 1 < len) load(rank_at(t + 1), bw, bg, bm);
+      finish(rank_at(t), aw, ag, am);
+      if (t + 1 >= len) break;
+      if (t + 2 < len) load(rank_at(t + 2), aw, ag, am);
+      finish(rank_at(t + 1), bw, bg, bm);
+    }
+  } else {
+    for (int32_t t = 1; t < len; ++t) {
+      v4f cw[U], cg[U], cm[U];
+      const int64_t rank = rank_at(t);
+      load(rank, cw, cg, cm);
+      finish(rank, cw, cg, cm);
+    }
+  }
+  // close the cycle
+  v4f out[U];
+  if (MODE == MODE_GRAD) {
+    v4f v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const v4f gbar = (first[u] + carry[u]) * 0.5f;
+      out[u] = local_update(fw[u], gbar, fm[u], a.lr, a.mu, v[u]);
+    }
+    store_one(a.m, rank0, v);
+  } else {
+#pragma unroll
+    for (int u = 0; u < U; ++u) out[u] = (first[u] + carry[u]) * 0.5f;
+  }
+  store_one(a.wn, rank0, out);
+}
+
 // ------------------------------------------------------------------- local update
 template <typename V, int U, bool NT, bool GUARD>
 __device__ __forceinline__ void sgd_tile(const step_args& a, int64_t x0, const V* w, const V* g, V* m, V* n) {
@@ -428,6 +629,7 @@ struct launch_ctx {
   const rank_table* rt;
   cycle_args ca;
   bool split;
+  int32_t rows_step, rows_waves, rows_chunks, rows_wg_per_cu;
 };
 
 // The lean kernels serve the default launch shape: 16-byte accesses, one chunk per
@@ -460,6 +662,31 @@ void launch_pair(const launch_ctx& lc, const step_args& a) {
     shifted = shifted || sh != 0;
   }
   dim3 grid = gd.grid;
+  if (lc.rows_step > 0 && NT) {
+    // row-aware tiling: a workgroup of W wavefronts, U chunks per thread, covers W*U tiles `step` apart
+    const int32_t Ur = lc.rows_chunks, Wv = lc.rows_waves;
+    int32_t log2_step = 0;
+    while ((1 << (log2_step + 1)) <= lc.rows_step) ++log2_step;
+    const int64_t step = int64_t(1) << log2_step;
+    const int64_t span = step * Wv * Ur;
+    int64_t gx = ((a.tiles + (shifted ? 1 : 0) + span - 1) / span) * step;
+    if (gx <= 0x7fffffffLL) {
+      grid.x = (unsigned)gx;
+      const dim3 block(64 * Wv);
+      uint32_t lds = 0;
+      if (lc.rows_wg_per_cu > 0) {
+        lds = (160u * 1024u / (uint32_t)lc.rows_wg_per_cu) & ~255u;
+        if (lds > 64u * 1024u - 4096u) lds = 64u * 1024u - 4096u;
+      }
+      switch (Ur) {
+        case 1: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 1>), grid, block, lds, lc.s, a, pt, log2_step); break;
+        case 2: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 2>), grid, block, lds, lc.s, a, pt, log2_step); break;
+        case 4: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 4>), grid, block, lds, lc.s, a, pt, log2_step); break;
+        default: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 8>), grid, block, lds, lc.s, a, pt, log2_step); break;
+      }
+      return;
+    }
+  }
   if (shifted) grid.x += 1;
   hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), grid, gd.block, gd.lds_bytes, lc.s, a, pt);
 }
@@ -474,6 +701,36 @@ void launch_cycle(const launch_ctx& lc, const step_args& a) {
   else
     hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, false>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca,
                        *lc.rt);
+}
+
+// Reserving more than 64 KB of dynamic LDS per workgroup needs the kernel's limit raised first.
+void allow_lds(const void* kernel, uint32_t bytes) {
+  if (bytes > 60u * 1024u)
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int MODE>
+void launch_walk(int U, bool ahead, dim3 grid, dim3 block, uint32_t lds, hipStream_t s, const step_args& a,
+                 const walk_args& wa, const rank_table& rt) {
+#define GG_CASE(UU)                                                                                       \
+  case UU:                                                                                                \
+    if (ahead) {                                                                                          \
+      allow_lds((const void*)gossip_cycle_walk_kernel<MODE, UU, true>, lds);                              \
+      hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, UU, true>), grid, block, lds, s, a, wa, rt);    \
+    } else {                                                                                              \
+      allow_lds((const void*)gossip_cycle_walk_kernel<MODE, UU, false>, lds);                             \
+      hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, UU, false>), grid, block, lds, s, a, wa, rt);   \
+    }                                                                                                     \
+    break;
+  switch (U) {
+    GG_CASE(1)
+    GG_CASE(2)
+    GG_CASE(4)
+    GG_CASE(8)
+    default:
+      GG_CASE(16)
+  }
+#undef GG_CASE
 }
 
 template <typename V, int U, bool NT>
@@ -582,7 +839,15 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
   const int32_t hop_group = ctx->tune.hop_group;
   bool split = kind == KIND_CYCLE && hop_group > 0 && cycle_len > hop_group + hop_group / 2;
   if (split && mode != MODE_GRAD) {
-    const int64_t need = rows * a.stride;  // one parking column per cycle
+    // One parking column per cycle.  The column is sized once for the phase that needs the
+    // most of them among all phases whose cycles are split, so later phases never regrow it.
+    int64_t max_rows = rows;
+    for (int32_t k = 0; k < ctx->L; ++k) {
+      const int32_t r_k = gcd32(p, int32_t(1) << k);
+      if (p / r_k > hop_group + hop_group / 2 && r_k > max_rows) max_rows = r_k;
+    }
+    int64_t need = max_rows * a.stride;
+    if (need > (int64_t(1) << 31)) need = rows * a.stride;
     if (need > (int64_t(1) << 31)) {
       split = false;  // would need more than 8 GiB of scratch: walk whole cycles instead
     } else if (need > ctx->carry_cap) {
@@ -597,6 +862,40 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
       ctx->carry_cap = need;
     }
   }
+  // Whole-chip lockstep walk of the aligned body (any cycle length, one launch).
+  const int32_t WU = ctx->tune.walk_tiles;
+  bool body_done = false;
+  if (kind == KIND_CYCLE && WU > 0 && body_hi > body_lo && nt) {
+    a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
+    const int64_t tiles = (a.rng.count + 63) / 64;
+    // a wavefront's U tiles are tile_step tiles apart; tile_step * U consecutive tiles form a block
+    const int64_t tstep = ctx->tune.walk_strided > 0 ? ctx->tune.walk_strided : 1;
+    int32_t WW = ctx->tune.walk_wg_waves;
+    if (WU >= 8) WW = 1;
+    while (WW * WU > 8 && WW > 1) WW /= 2;
+    const int64_t gx = (tiles + tstep * WU * WW - 1) / (tstep * WU * WW) * tstep;
+    if (gx <= 0x7fffffffLL) {
+      walk_args wa;
+      wa.cycle_len = cycle_len;
+      wa.hop_barrier = (ctx->tune.walk_barrier && WW > 1) ? 1 : 0;
+      wa.tile_mul = tstep * WU * WW;
+      wa.tile_step = tstep;
+      const dim3 grid((unsigned)gx, (unsigned)rows, 1);
+      const dim3 block(64 * WW);
+      const bool ahead = ctx->tune.walk_ahead != 0;
+      uint32_t lds = 0;
+      if (ctx->tune.walk_waves > 0) lds = (160u * 1024u / (uint32_t)ctx->tune.walk_waves) & ~255u;
+      if (mode == MODE_SYNC)
+        launch_walk<MODE_SYNC>(WU, ahead, grid, block, lds, s, a, wa, rt);
+      else if (mode == MODE_STALE)
+        launch_walk<MODE_STALE>(WU, ahead, grid, block, lds, s, a, wa, rt);
+      else
+        launch_walk<MODE_GRAD>(WU, ahead, grid, block, lds, s, a, wa, rt);
+      GG_HIP_TRY(hipGetLastError());
+      body_done = true;  // what is left is the ragged edge
+      split = false;
+    }
+  }
   const int32_t groups = split ? (cycle_len + hop_group - 1) / hop_group : 1;
   for (int32_t gi = groups - 1; gi >= 0; --gi) {
     cycle_args ca;
@@ -604,18 +903,18 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
     ca.t_begin = split ? gi * hop_group : 0;
     ca.t_end = split ? (ca.t_begin + hop_group < cycle_len ? ca.t_begin + hop_group : cycle_len) : cycle_len;
     ca.carry = ctx->d_carry;
-    if (body_hi > body_lo) {
+    if (body_hi > body_lo && !body_done) {
       int U = ctx->tune.chunks;
       if (kind == KIND_CYCLE && U > 2) U = 2;
       a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
-      launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, loads), s, &pt, &rt, ca, split};
+      launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, loads), s, &pt, &rt, ca, split, ctx->tune.rows_step, ctx->tune.rows_waves, ctx->tune.rows_chunks, ctx->tune.rows_wg_per_cu};
       a.tiles = lc.gd.tiles;
       launch_any<v4f>(kind, mode, U, nt, lc, a);
       GG_HIP_TRY(hipGetLastError());
     }
     if (edge > 0) {
       a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
-      launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, loads), s, &pt, &rt, ca, split};
+      launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, loads), s, &pt, &rt, ca, split, 0, 1, 1, 0};
       a.tiles = lc.gd.tiles;
       launch_any<float>(kind, mode, 1, nt, lc, a);
       GG_HIP_TRY(hipGetLastError());

@@ -61,6 +61,16 @@ struct gg_tuning {
   int32_t blocks_per_cu;  // 0: no cap; >0: at most this many resident workgroups per CU (LDS reservation)
   int32_t nontemporal;    // 1: streaming (nt) loads and stores
   int32_t hop_group;      // dissemination: hops per launch on long cycles (0: never split)
+  int32_t walk_tiles;     // dissemination: tiles per wavefront of the lockstep walk (0: off; 2, 4, 8, 16)
+  int32_t walk_ahead;     // lockstep walk: load the next rank before finishing the current one
+  int32_t walk_strided;   // lockstep walk: a wavefront's tiles are grid-strided instead of contiguous
+  int32_t walk_waves;     // lockstep walk: cap on resident wavefronts per CU (0: none)
+  int32_t walk_wg_waves;  // lockstep walk: wavefronts per workgroup (1, 2, 4, 8)
+  int32_t walk_barrier;   // lockstep walk: barrier after every hop
+  int32_t rows_step;      // row-aware tiling: tiles between the tiles of one workgroup (0: off; power of two)
+  int32_t rows_waves;     // row-aware tiling: wavefronts per workgroup (1, 2, 4, 8)
+  int32_t rows_chunks;    // row-aware tiling: chunks per thread (1, 2, 4, 8); waves * chunks <= 8
+  int32_t rows_wg_per_cu; // row-aware tiling: cap on resident workgroups per CU (0: none)
 };
 
 struct gg_ctx {

@@ -141,3 +141,90 @@ def test_config3_segments_and_allreduce_comparator_sampled_windows():
     # any size: after the all-reduce every rank holds the same gradient bits
     assert torch.equal(Ga[0, :n], Ga[p - 1, :n])
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# The configured step counts, the paper's preferred topology and gradient averaging at full size
+# ---------------------------------------------------------------------------------------------
+def _sampled(W, G, M, n, num_random):
+    cols = _columns(n, num_random)
+    cd = torch.as_tensor(cols, device=DEV)
+    return cd, _take(W, cd), _take(G, cd), _take(M, cd)
+
+
+def _assert_bit_equal(cd, Wdev, Mdev, Wo, Mo, what):
+    dw = assert_close_fp32(_take(Wdev, cd), Wo, "W " + what)
+    dm = assert_close_fp32(_take(Mdev, cd), Mo, "M " + what)
+    assert dw == 0 and dm == 0, "%s: differing bits W %d, M %d" % (what, dw, dm)
+
+
+def _run_full(p, steps, checkpoints, topology=gg.TOPO_HYPERCUBE, staleness=0, avg_mode=gg.AVG_MODEL,
+              double_buffer=False, num_random=64, shuffle=False, seed=0):
+    """Run `steps` consecutive steps at N = 25,557,032 on the GPU and on the sampled-window
+    oracle, comparing at every step listed in `checkpoints` (steps already done) and at the end."""
+    from oracle import shuffle as sh
+    n = gg_synth.RESNET50_PARAMS
+    stride = _bench_stride(n)
+    W, G, M = gg_synth.make_state(p, n, stride, seed=seed, device=DEV)
+    cd, Wo, Go, Mo = _sampled(W, G, M, n, num_random)
+    ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=seed, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM,
+                     topology=topology, staleness=staleness, avg_mode=avg_mode)
+    bufs = [W, torch.full_like(W, float("nan")) if double_buffer else None]
+    cur = 0
+    if shuffle:
+        off = sh.block_offsets(gg_synth.IMAGENET1K_TRAIN, p)
+        idx = gg_synth.make_indices(gg_synth.IMAGENET1K_TRAIN, DEV)
+        idx_o = sh.initial_indices(gg_synth.IMAGENET1K_TRAIN)
+    otopo = sc.HYPERCUBE if topology == gg.TOPO_HYPERCUBE else sc.DISSEMINATION
+    for t in range(steps):
+        if double_buffer:
+            ctx.gossip_step(t, bufs[cur], G, M, w_next=bufs[cur ^ 1])
+            cur ^= 1
+        else:
+            ctx.gossip_step(t, W, G, M)
+        send, recv = sc.partners(p, seed, p, otopo, t)
+        gs, gr = ctx.partner(t)
+        assert gs.tolist() == send and gr.tolist() == recv
+        og.gossip_step(Wo, Go, Mo, recv, gg_synth.LR, gg_synth.MOMENTUM, avg_mode=avg_mode,
+                       W_stale=Wo.copy() if staleness else None)
+        if shuffle:
+            ctx.shuffle(t, gg.SHUF_PARTNER_SWAP, idx, off)
+            sh.partner_swap_step(idx_o, off, recv, seed, t)
+        if t + 1 in checkpoints or t + 1 == steps:
+            torch.cuda.synchronize()
+            _assert_bit_equal(cd, bufs[cur], M, Wo, Mo, "after %d steps" % (t + 1))
+            if shuffle:
+                assert np.array_equal(idx.cpu().numpy(), idx_o), "indices after %d steps" % (t + 1)
+    assert np.array_equal(_take(G, cd), Go)              # g is never written
+    if not double_buffer:
+        assert torch.count_nonzero(W[:, n:]) == 0        # padding untouched
+    assert torch.count_nonzero(M[:, n:]) == 0
+    ctx.close()
+    return bufs[cur]
+
+
+@pytest.mark.parametrize("staleness", [0, 1])
+def test_config4_all_64_steps(staleness):
+    # the configured run: 64 consecutive steps, i.e. communicators 0..10 of the 64, L = 6;
+    # staleness 1 goes through the double buffer
+    _run_full(64, 64, checkpoints=(1, 31), staleness=staleness, double_buffer=bool(staleness))
+
+
+def test_config5_all_128_steps_with_shuffle_every_step():
+    # the configured run: 128 consecutive steps (communicators 0..18, L = 7), the partner-swap
+    # shuffle of the 1,281,167 ids at every step
+    _run_full(128, 128, checkpoints=(1, 64), shuffle=True, num_random=48)
+
+
+@pytest.mark.parametrize("staleness,double_buffer", [(0, False), (0, True), (1, False), (1, True)])
+def test_config4_shape_dissemination(staleness, double_buffer):
+    # the paper's preferred topology (Sec. 4.4.2) at p = 64 x ResNet50-sized rows: 2L + 2 = 14 steps
+    # cover every phase twice (long cycles included) and cross into two shuffled communicators
+    _run_full(64, 14, checkpoints=(1, 6, 7), topology=gg.TOPO_DISSEMINATION, staleness=staleness,
+              double_buffer=double_buffer)
+
+
+@pytest.mark.parametrize("topology", [gg.TOPO_HYPERCUBE, gg.TOPO_DISSEMINATION])
+def test_config4_shape_gradient_averaging(topology):
+    # the gradient-buffer reading of the exchange (Sec. 5) at p = 64 x ResNet50-sized rows
+    _run_full(64, 14, checkpoints=(1, 7), topology=topology, avg_mode=gg.AVG_GRAD)
