@@ -27,8 +27,7 @@
  *     be replayed.
  *   - A context is not thread-safe: call it from one host thread at a time.  Calls
  *     may target different streams; work that shares the context's scratch
- *     (two gg_shuffle calls, two split dissemination steps) must be ordered by the
- *     caller.
+ *     (two gg_shuffle calls) must be ordered by the caller.
  *   - All [p][.] buffers share one layout: rank j starts at element
  *     j * rank_stride, its n parameters are contiguous, rank_stride >= n.
  *     Buffers whose base address and rank_stride*4 are multiples of 16 bytes take
@@ -64,8 +63,7 @@ enum { GG_SHUF_PARTNER_SWAP = 0, GG_SHUF_RING = 1 };
 
 #define GG_MAX_RANKS 1024
 
-typedef struct gg_ctx gg_ctx; /* opaque; owns only its schedule tables and scratch (shuffle lists,
-                                 dissemination carry column) */
+typedef struct gg_ctx gg_ctx; /* opaque; owns only its schedule tables and the shuffle's scratch */
 
 typedef struct {
   int32_t p;           /* virtual ranks, 2 .. GG_MAX_RANKS; power of two for hypercube     */
@@ -106,10 +104,9 @@ int gg_destroy(gg_ctx* ctx);
  * send_to: host int32[p], required.  recv_from: host int32[p] or NULL.  step >= 0. */
 int gg_partner(const gg_ctx* ctx, int64_t step, int32_t* send_to, int32_t* recv_from);
 
-/* One GossipGraD step for all p ranks (Eq. 1-2 + Sec. 6), update and average fused
- * (one launch; dissemination phases whose partner cycles are longer than 12 ranks
- * take one launch per group of 8 hops, and the first such call allocates a
- * context-owned carry column, which synchronises the device once):
+/* One GossipGraD step for all p ranks (Eq. 1-2 + Sec. 6), update and average fused in
+ * one launch (plus one scalar launch for a ragged or unaligned remainder); allocates
+ * nothing and never synchronises:
  *     v = mu*m + lr*g ;  m <- v ;  T = w - v ;  w_new[j] = (T[j] + X[c(j)]) / 2
  * with c = the step's partner map (hypercube: the pair partner; dissemination:
  * the rank j receives from), X = T (staleness 0) or the entry weights w
@@ -173,30 +170,6 @@ int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
  * for the vector path); sample_bytes > 0, multiple of 4; 0 <= batch <= min n_j. */
 int gg_shuffle_payload(gg_ctx* ctx, int64_t step, void* payload, int64_t sample_bytes,
                        const int64_t* rank_offsets, int32_t batch, void* stream);
-
-/* Measurement aid: plain device-to-device copy kernel (16-byte loads/stores) used
- * to calibrate achievable memory bandwidth next to the gossip kernel.  dst, src:
- * device, 16-byte aligned, nbytes a multiple of 16. */
-int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream);
-
-/* Measurement aid: an arithmetic-only kernel (no memory traffic) that stands in
- * for the forward/backward computation when the overlap of the layer-wise
- * exchange with computation (Sec. 5, Sec. 5.1) is measured.  Runs `blocks`
- * workgroups of 256 threads, each thread a dependent chain of `iters`
- * multiply-adds.  sink: device float[1], written only if the chain ends on an
- * impossible value (keeps the loop alive).  1 <= blocks <= 65536, iters >= 0. */
-int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream);
-
-/* Launch-shape knobs for bandwidth sweeps (never change results).  key:
- *   0 = threads per workgroup (64, 128 or 256; default 64),
- *   1 = 16-byte chunks per thread per tile (1, 2, 4, 8; default 1),
- *   2 = cap on resident workgroups per CU, enforced by reserving LDS
- *       (0 = no cap, 3..64; default 7: few waves in flight keep the DRAM
- *       row-buffer working set small, which is what the streaming kernels want),
- *   3 = non-temporal loads/stores (0/1; default 1),
- *   4 = dissemination: hops per launch when a long partner cycle is walked in
- *       groups (0 = always one launch, 2..1024; default 8). */
-int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value);
 
 /* Static, never NULL. */
 const char* gg_strerror(int code);

@@ -5,6 +5,7 @@ ctypes binding (binding.py).  There is no fallback implementation.
 """
 from .binding import (  # noqa: F401
     AVG_GRAD, AVG_MODEL, AVG_NONE, Context, GGConfig, GGError, LIB_PATH, MAX_RANKS, SHUF_PARTNER_SWAP,
-    SHUF_RING, TOPO_DISSEMINATION, TOPO_HYPERCUBE, TUNE_BLOCKS_PER_CU, TUNE_CHUNKS, TUNE_HOP_GROUP, TUNE_NONTEMPORAL,
-    TUNE_THREADS, TUNE_WALK_AHEAD, TUNE_WALK_STRIDED, TUNE_WALK_TILES, aligned_stride, busy_probe, copy_probe, lib,
+    SHUF_RING, TOPO_DISSEMINATION, TOPO_HYPERCUBE, TUNE_BLOCKS_PER_CU, TUNE_CHUNKS, TUNE_NONTEMPORAL,
+    TUNE_THREADS, TUNE_WALK_BARRIER, TUNE_WALK_CHUNKS, TUNE_WALK_GROUP_LOG2, TUNE_WALK_STEP, TUNE_WALK_WAVES, TUNE_WALK_WG_PER_CU,
+    aligned_stride, busy_probe, copy_probe, lib, stream_probe,
 )

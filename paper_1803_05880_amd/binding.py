@@ -21,8 +21,9 @@ TOPO_HYPERCUBE, TOPO_DISSEMINATION = 0, 1
 AVG_MODEL, AVG_GRAD, AVG_NONE = 0, 1, 2
 SHUF_PARTNER_SWAP, SHUF_RING = 0, 1
 MAX_RANKS = 1024
-TUNE_THREADS, TUNE_CHUNKS, TUNE_BLOCKS_PER_CU, TUNE_NONTEMPORAL, TUNE_HOP_GROUP = 0, 1, 2, 3, 4
-TUNE_WALK_TILES, TUNE_WALK_AHEAD, TUNE_WALK_STRIDED = 5, 6, 7
+TUNE_THREADS, TUNE_CHUNKS, TUNE_BLOCKS_PER_CU, TUNE_NONTEMPORAL = 0, 1, 2, 3
+TUNE_WALK_CHUNKS, TUNE_WALK_WAVES, TUNE_WALK_STEP, TUNE_WALK_WG_PER_CU, TUNE_WALK_BARRIER = 4, 5, 6, 7, 8
+TUNE_WALK_GROUP_LOG2 = 9
 
 
 def aligned_stride(n, elements=1024):
@@ -83,12 +84,13 @@ def lib():
         L.gg_shuffle_payload.argtypes = [vp, i64, vp, i64, vp, i32, vp]
         L.gg_copy_probe.argtypes = [vp, vp, i64, vp]
         L.gg_busy_probe.argtypes = [i64, i32, vp, vp]
+        L.gg_stream_probe.argtypes = [i64, i32, vp, i64, vp]
         L.gg_set_tuning.argtypes = [vp, i32, i32]
         L.gg_strerror.argtypes = [ctypes.c_int]
         L.gg_strerror.restype = ctypes.c_char_p
         for name in ("gg_init", "gg_destroy", "gg_set_hyper", "gg_partner", "gg_gossip_step", "gg_sgd_step",
                      "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_shuffle_payload", "gg_copy_probe",
-                     "gg_busy_probe", "gg_set_tuning"):
+                     "gg_busy_probe", "gg_stream_probe", "gg_set_tuning"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -212,3 +214,9 @@ def busy_probe(iters, blocks, sink, stream=None):
     """gg_busy_probe: arithmetic-only stand-in for forward/backward computation."""
     _check(lib().gg_busy_probe(int(iters), int(blocks), _dev_ptr(sink, torch.float32, "sink"), _stream_ptr(stream)),
            "gg_busy_probe")
+
+
+def stream_probe(iters, blocks, buf, stream=None):
+    """gg_stream_probe: stand-in for forward/backward computation that also streams memory."""
+    _check(lib().gg_stream_probe(int(iters), int(blocks), ctypes.c_void_p(buf.data_ptr()),
+                                 buf.numel() * buf.element_size(), _stream_ptr(stream)), "gg_stream_probe")

@@ -1,6 +1,5 @@
 // Recursive-doubling all-reduce over the virtual ranks (Sec. 3.1, Sec. 4.1): the
-// Theta(log p) method GossipGraD is compared with, plus its one-pass form and a
-// plain copy kernel for bandwidth calibration.
+// Theta(log p) method GossipGraD is compared with, plus its one-pass form.
 #pragma clang fp contract(off)
 
 #include "gg_internal.h"
@@ -75,6 +74,7 @@ struct tree_sum<0, V, NT> {
 
 // One pass: read the p values of a chunk once, add them in tree order, write the
 // result to every rank: 8 B / rank / element in total instead of 8 B per round.
+// General form (scalar instantiation for ragged or unaligned buffers).
 template <int K, typename V, bool NT>
 __global__ void __launch_bounds__(256) allreduce_onepass_kernel(ar_args a) {
   for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
@@ -87,16 +87,69 @@ __global__ void __launch_bounds__(256) allreduce_onepass_kernel(ar_args a) {
   }
 }
 
-__global__ void __launch_bounds__(256) copy_kernel(v4f* dst, const v4f* src, int64_t count) {
-  const int64_t step = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += step)
-    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
-}
+// Default form for 16-byte aligned buffers: the same tree, walked so that the chip
+// streams a few ranks at a time instead of all p.  A workgroup of W wavefronts owns
+// W*U tiles `step` tiles apart (32 KB: same DRAM channel, eight of them one DRAM row),
+// visits the ranks in order 2^B at a time and passes a barrier after each such group,
+// first reading (partial sums wait on a register stack of depth K), then writing.
+struct walk_shape {
+  int32_t step;
+  int32_t barrier;
+};
 
-__global__ void __launch_bounds__(256) busy_kernel(int64_t iters, float* sink) {
-  float x = 1.0f + (float)threadIdx.x * 1e-7f, y = 0.999999f;
-  for (int64_t i = 0; i < iters; ++i) x = x * y + 1e-9f;
-  if (x == -1.0f) *sink = x;  // never true: the chain stays positive
+template <int K, int B, int U>
+struct tree_walk {
+  static __device__ __forceinline__ void run(const ar_args& a, const walk_shape& ws, const int64_t* idx,
+                                             const bool* on, int64_t r, v4f* out) {
+    v4f lo[U], hi[U];
+    tree_walk<K - 1, B, U>::run(a, ws, idx, on, r, lo);
+    tree_walk<K - 1, B, U>::run(a, ws, idx, on, r + (int64_t(1) << (K - 1)), hi);
+#pragma unroll
+    for (int u = 0; u < U; ++u) out[u] = lo[u] + hi[u];
+    // every wavefront of the workgroup passes here once per group of 2^B ranks
+    if (K == B && ws.barrier) __syncthreads();
+  }
+};
+template <int B, int U>
+struct tree_walk<0, B, U> {
+  static __device__ __forceinline__ void run(const ar_args& a, const walk_shape& ws, const int64_t* idx,
+                                             const bool* on, int64_t r, v4f* out) {
+    const v4f* row = reinterpret_cast<const v4f*>(a.g + r * a.stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (on[u]) out[u] = gg_ld<true>(row + idx[u]);
+    if (B == 0 && ws.barrier) __syncthreads();
+  }
+};
+
+template <int K, int B, int U>
+__global__ void __launch_bounds__(512 / U) allreduce_walk_kernel(ar_args a, walk_shape ws) {
+  int64_t idx[U];
+  bool on[U];
+  {
+    const int64_t bx = blockIdx.x, step = ws.step;
+    const int64_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63, W = blockDim.x >> 6;
+    const int64_t tile0 = (bx / step) * (step * W * U) + bx % step + wave * U * step;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t x = (tile0 + u * step) * 64 + lane;
+      on[u] = x < a.rng.count;
+      idx[u] = a.rng.lo + x;
+    }
+  }
+  v4f s[U];
+  tree_walk<K, (B < K ? B : K), U>::run(a, ws, idx, on, 0, s);
+  if (a.scaled) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) s[u] = s[u] * a.scale;
+  }
+  for (int64_t r = 0; r < (int64_t(1) << K); ++r) {
+    v4f* row = reinterpret_cast<v4f*>(a.g + r * a.stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (on[u]) __builtin_nontemporal_store(s[u], row + idx[u]);
+    if (ws.barrier && ((r + 1) & ((int64_t(1) << B) - 1)) == 0) __syncthreads();
+  }
 }
 
 template <typename V>
@@ -135,6 +188,34 @@ void launch_onepass(int K, const gg_grid& gd, hipStream_t s, const ar_args& a) {
       GG_CASE(7)
   }
 #undef GG_CASE
+}
+
+template <int B, int U>
+void launch_walk_k(int K, dim3 grid, dim3 block, uint32_t lds, hipStream_t s, const ar_args& a, const walk_shape& ws) {
+#define GG_CASE(KK)                                                                              \
+  case KK:                                                                                       \
+    hipLaunchKernelGGL((allreduce_walk_kernel<KK, B, U>), grid, block, lds, s, a, ws);           \
+    break;
+  switch (K) {
+    GG_CASE(1)
+    GG_CASE(2)
+    GG_CASE(3)
+    GG_CASE(4)
+    GG_CASE(5)
+    GG_CASE(6)
+    default:
+      GG_CASE(7)
+  }
+#undef GG_CASE
+}
+
+template <int B>
+void launch_walk_u(int U, int K, dim3 grid, dim3 block, uint32_t lds, hipStream_t s, const ar_args& a,
+                   const walk_shape& ws) {
+  if (U == 1)
+    launch_walk_k<B, 1>(K, grid, block, lds, s, a, ws);
+  else
+    launch_walk_k<B, 2>(K, grid, block, lds, s, a, ws);  // more chunks spill the register stack of partial sums
 }
 
 enum { MAX_ONEPASS_LOG2 = 7 };
@@ -207,9 +288,24 @@ extern "C" int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void
   a.scale = 1.0f / (float)ctx->cfg.p;
   if (sp.body.count > 0) {
     a.rng = sp.body;
-    gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1, 12);
-    a.tiles = gd.tiles;
-    launch_onepass<v4f>(ctx->L, gd, (hipStream_t)stream, a);
+    // measured best at p = 64 x 25.6 M parameters: 4 wavefronts x 2 chunks, a barrier every 4 ranks
+    const gg_walk_shape own{2, 4, 32, 0, 1, 2};
+    const gg_walk_launch wl = gg_walk_geometry(ctx, own, 2, (a.rng.count + 63) / 64);
+    if (wl.grid_x > 0) {
+      walk_shape ws{wl.shape.step, wl.shape.barrier};
+      const dim3 grid((unsigned)wl.grid_x), block(64u * (unsigned)wl.shape.waves);
+      const int U = wl.shape.chunks;
+      switch (wl.shape.group_log2) {
+        case 0: launch_walk_u<0>(U, ctx->L, grid, block, wl.lds_bytes, (hipStream_t)stream, a, ws); break;
+        case 1: launch_walk_u<1>(U, ctx->L, grid, block, wl.lds_bytes, (hipStream_t)stream, a, ws); break;
+        case 2: launch_walk_u<2>(U, ctx->L, grid, block, wl.lds_bytes, (hipStream_t)stream, a, ws); break;
+        default: launch_walk_u<3>(U, ctx->L, grid, block, wl.lds_bytes, (hipStream_t)stream, a, ws); break;
+      }
+    } else {
+      gg_grid gd = gg_make_grid(ctx, a.rng.count, 1, 1, 12);
+      a.tiles = gd.tiles;
+      launch_onepass<v4f>(ctx->L, gd, (hipStream_t)stream, a);
+    }
     GG_HIP_TRY(hipGetLastError());
   }
   if (sp.edge.count > 0) {
@@ -219,28 +315,5 @@ extern "C" int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void
     launch_onepass<float>(ctx->L, gd, (hipStream_t)stream, a);
     GG_HIP_TRY(hipGetLastError());
   }
-  return GG_OK;
-}
-
-extern "C" int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream) {
-  if (!dst || !src || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
-  if (!gg_aligned(dst, 16) || !gg_aligned(src, 16)) return GG_ERR_ALIGN;
-  if (nbytes == 0) return GG_OK;
-  // one wavefront per workgroup, one 16-byte chunk per thread, no occupancy cap: the
-  // shape that copies fastest on this part
-  const int64_t count = nbytes / 16;
-  int64_t blocks = (count + 63) / 64;
-  if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
-  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(64), 0, (hipStream_t)stream, (v4f*)dst,
-                     (const v4f*)src, count);
-  GG_HIP_TRY(hipGetLastError());
-  return GG_OK;
-}
-
-extern "C" int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream) {
-  if (!sink || iters < 0 || blocks < 1 || blocks > 65536) return GG_ERR_ARG;
-  if (!gg_aligned(sink, 4)) return GG_ERR_ALIGN;
-  hipLaunchKernelGGL(busy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, iters, sink);
-  GG_HIP_TRY(hipGetLastError());
   return GG_OK;
 }

@@ -77,6 +77,34 @@ gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t r
   return out;
 }
 
+gg_walk_launch gg_walk_geometry(const gg_ctx* ctx, const gg_walk_shape& d, int32_t max_chunks, int64_t tiles) {
+  const gg_walk_shape& t = ctx->tune.walk;
+  gg_walk_launch out;
+  gg_walk_shape& sh = out.shape;
+  sh.chunks = t.chunks == GG_WALK_UNSET ? d.chunks : t.chunks;
+  sh.waves = t.waves == GG_WALK_UNSET ? d.waves : t.waves;
+  sh.step = t.step == GG_WALK_UNSET ? d.step : t.step;
+  sh.wg_per_cu = t.wg_per_cu == GG_WALK_UNSET ? d.wg_per_cu : t.wg_per_cu;
+  sh.barrier = t.barrier == GG_WALK_UNSET ? d.barrier : t.barrier;
+  sh.group_log2 = t.group_log2 == GG_WALK_UNSET ? d.group_log2 : t.group_log2;
+  if (sh.chunks > max_chunks) sh.chunks = max_chunks;
+  while (sh.chunks * sh.waves > 8) sh.waves /= 2;  // an override of one may meet the default of the other
+  if (sh.waves == 1) sh.barrier = 0;
+  out.grid_x = 0;
+  out.lds_bytes = 0;
+  if (sh.chunks <= 0 || !ctx->tune.nontemporal) return out;
+  const int64_t span = (int64_t)sh.step * sh.waves * sh.chunks;
+  const int64_t gx = (tiles + span - 1) / span * sh.step;
+  if (gx < 1 || gx > 0x7fffffffLL) return out;
+  out.grid_x = gx;
+  if (sh.wg_per_cu > 0) {
+    uint32_t b = (160u * 1024u / (uint32_t)sh.wg_per_cu) & ~255u;
+    if (b > 64u * 1024u - 4096u) b = 64u * 1024u - 4096u;  // stay below the default dynamic-LDS limit
+    out.lds_bytes = b;
+  }
+  return out;
+}
+
 extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
   if (!cfg || !out) return GG_ERR_ARG;
   if (cfg->p < 2 || cfg->p > GG_MAX_RANKS) return GG_ERR_ARG;
@@ -101,9 +129,7 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
   ctx->scratch_cap = 0;
   ctx->d_offsets = nullptr;
   ctx->h_offsets_pinned = nullptr;
-  ctx->tune = gg_tuning{64, 1, 7, 1, 8, 0, 1, 0, 0, 1, 0, 0, 1, 1, 0};
-  ctx->d_carry = nullptr;
-  ctx->carry_cap = 0;
+  ctx->tune = gg_tuning{64, 1, 7, 1, gg_walk_shape{GG_WALK_UNSET, GG_WALK_UNSET, GG_WALK_UNSET, GG_WALK_UNSET, GG_WALK_UNSET, GG_WALK_UNSET}};
 
   const size_t entries = (size_t)ctx->R * (size_t)cfg->p;
   try {
@@ -170,7 +196,6 @@ extern "C" int gg_destroy(gg_ctx* ctx) {
   if (hipDeviceSynchronize() != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->d_sigma && hipFree(ctx->d_sigma) != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->d_scratch && hipFree(ctx->d_scratch) != hipSuccess) rc = GG_ERR_HIP;
-  if (ctx->d_carry && hipFree(ctx->d_carry) != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->d_offsets && hipFree(ctx->d_offsets) != hipSuccess) rc = GG_ERR_HIP;
   if (ctx->h_offsets_pinned && hipHostFree(ctx->h_offsets_pinned) != hipSuccess) rc = GG_ERR_HIP;
   if (rc != GG_OK) (void)hipGetLastError();
@@ -198,76 +223,6 @@ extern "C" int gg_partner(const gg_ctx* ctx, int64_t step, int32_t* send_to, int
     }
   }
   return GG_OK;
-}
-
-extern "C" int gg_set_tuning(gg_ctx* ctx, int32_t key, int32_t value) {
-  if (!ctx) return GG_ERR_ARG;
-  switch (key) {
-    case 0:
-      if (value != 64 && value != 128 && value != 256) return GG_ERR_ARG;
-      ctx->tune.threads = value;
-      return GG_OK;
-    case 1:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return GG_ERR_ARG;
-      ctx->tune.chunks = value;
-      return GG_OK;
-    case 2:
-      if (value != 0 && (value < 3 || value > 64)) return GG_ERR_ARG;
-      ctx->tune.blocks_per_cu = value;
-      return GG_OK;
-    case 3:
-      if (value != 0 && value != 1) return GG_ERR_ARG;
-      ctx->tune.nontemporal = value;
-      return GG_OK;
-    case 4:
-      if (value < 0 || value == 1 || value > GG_MAX_RANKS) return GG_ERR_ARG;
-      ctx->tune.hop_group = value;
-      return GG_OK;
-    case 13:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return GG_ERR_ARG;
-      ctx->tune.walk_wg_waves = value;
-      return GG_OK;
-    case 14:
-      if (value != 0 && value != 1) return GG_ERR_ARG;
-      ctx->tune.walk_barrier = value;
-      return GG_OK;
-    case 5:
-      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return GG_ERR_ARG;
-      ctx->tune.walk_tiles = value;
-      return GG_OK;
-    case 6:
-      if (value != 0 && value != 1) return GG_ERR_ARG;
-      ctx->tune.walk_ahead = value;
-      return GG_OK;
-    case 7:
-      if (value < 0 || value > 65536) return GG_ERR_ARG;
-      ctx->tune.walk_strided = value;
-      return GG_OK;
-    case 8:
-      if (value < 0 || value > 64) return GG_ERR_ARG;
-      ctx->tune.walk_waves = value;
-      return GG_OK;
-    case 9:
-      if (value < 0 || value > 4096 || (value & (value - 1))) return GG_ERR_ARG;
-      ctx->tune.rows_step = value;
-      return GG_OK;
-    case 10:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return GG_ERR_ARG;
-      if (value * ctx->tune.rows_chunks > 8) return GG_ERR_ARG;
-      ctx->tune.rows_waves = value;
-      return GG_OK;
-    case 11:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return GG_ERR_ARG;
-      if (value * ctx->tune.rows_waves > 8) return GG_ERR_ARG;
-      ctx->tune.rows_chunks = value;
-      return GG_OK;
-    case 12:
-      if (value != 0 && (value < 3 || value > 64)) return GG_ERR_ARG;
-      ctx->tune.rows_wg_per_cu = value;
-      return GG_OK;
-    default:
-      return GG_ERR_ARG;
-  }
 }
 
 extern "C" const char* gg_strerror(int code) {

@@ -182,72 +182,6 @@ __global__ void __launch_bounds__(64) gossip_pair_lean_kernel(step_args a, pair_
   }
 }
 
-// Row-aware form of the lean kernel.  Device memory interleaves consecutive 128-byte
-// pieces over its channels, so addresses 32 KB apart fall into the same channel and, eight
-// of them, into one DRAM row.  A workgroup therefore takes tiles that are `1 << log2_step`
-// tiles (32 KB by default) apart -- wavefront w, chunk u handles tile
-//   (blockIdx.x >> log2_step) * (step * W * U) + (blockIdx.x & (step - 1)) + (w * U + u) * step
-// -- and touches each row it opens W * U times at once instead of once, while consecutive
-// workgroups still take consecutive tiles.
-template <int MODE, int U>
-__global__ void __launch_bounds__(512 / U) gossip_pair_rows_kernel(step_args a, pair_table pt, int32_t log2_step) {
-  const uint32_t jc = pt.jc[blockIdx.y];
-  const int64_t j = jc & 0x3ffu;
-  const int64_t c = (jc >> 10) & 0x3ffu;
-  const int64_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t W = blockDim.x >> 6;
-  const int64_t bx = blockIdx.x;
-  const int64_t tile0 = (((bx >> log2_step) * W * U + wave * U) << log2_step) + (bx & ((int64_t(1) << log2_step) - 1));
-  const v4f* wj = reinterpret_cast<const v4f*>(a.w + j * a.stride);
-  const v4f* wc = reinterpret_cast<const v4f*>(a.w + c * a.stride);
-  const v4f* gj = reinterpret_cast<const v4f*>(a.g + j * a.stride);
-  const v4f* gc = reinterpret_cast<const v4f*>(a.g + c * a.stride);
-  v4f* mj = reinterpret_cast<v4f*>(a.m + j * a.stride);
-  v4f* mc = reinterpret_cast<v4f*>(a.m + c * a.stride);
-  v4f* nj = reinterpret_cast<v4f*>(a.wn + j * a.stride);
-  v4f* nc = reinterpret_cast<v4f*>(a.wn + c * a.stride);
-  int64_t i[U];
-  bool on[U];
-  v4f Wj[U], Wc[U], Gj[U], Gc[U], Mj[U], Mc[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    i[u] = a.rng.lo + ((tile0 + ((int64_t)u << log2_step)) << 6) + lane - (int64_t)(jc >> 20);
-    on[u] = i[u] >= a.rng.lo && i[u] < a.rng.lo + a.rng.count;
-    if (on[u]) {
-      Wj[u] = gg_ld<true>(wj + i[u]);
-      Wc[u] = gg_ld<true>(wc + i[u]);
-      Gj[u] = gg_ld<true>(gj + i[u]);
-      Gc[u] = gg_ld<true>(gc + i[u]);
-      Mj[u] = gg_ld<true>(mj + i[u]);
-      Mc[u] = gg_ld<true>(mc + i[u]);
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    if (!on[u]) continue;
-    v4f vj, vc, outj, outc;
-    if (MODE == MODE_GRAD) {
-      const v4f gbar = (Gj[u] + Gc[u]) * 0.5f;
-      outj = local_update(Wj[u], gbar, Mj[u], a.lr, a.mu, vj);
-      outc = local_update(Wc[u], gbar, Mc[u], a.lr, a.mu, vc);
-    } else {
-      const v4f Tj = local_update(Wj[u], Gj[u], Mj[u], a.lr, a.mu, vj);
-      const v4f Tc = local_update(Wc[u], Gc[u], Mc[u], a.lr, a.mu, vc);
-      if (MODE == MODE_SYNC) {
-        outj = (Tj + Tc) * 0.5f;
-        outc = outj;
-      } else {
-        outj = (Tj + Wc[u]) * 0.5f;
-        outc = (Tc + Wj[u]) * 0.5f;
-      }
-    }
-    st_stream(nj + i[u], outj);
-    st_stream(nc + i[u], outc);
-    st_stream(mj + i[u], vj);
-    st_stream(mc + i[u], vc);
-  }
-}
-
 // ------------------------------------------------------------ dissemination cycles
 // At phase k virtual rank v receives from v - 2^k (mod p).  The map splits the
 // ranks into gcd(p, 2^k) cycles v0, v0+2^k, v0+2*2^k, ...; grid row = cycle.  One
@@ -263,20 +197,10 @@ struct rank_table {
   uint32_t r2[GG_MAX_RANKS / 2];
 };
 
-// A long cycle keeps 5 address streams open per rank on it, and bandwidth falls
-// with the number of streams touched at once.  SPLIT cuts the walk into groups
-// of consecutive hops, one launch per group, LAST group first: a group's
-// carry-in is recomputed from the (still untouched) rank before it, and the
-// contribution of the cycle's last rank to its first is parked in a carry column
-// by the first launch and picked up by the last one.
-struct cycle_args {
-  int32_t cycle_len;
-  int32_t t_begin, t_end;  // hops handled by this launch (whole cycle when not split)
-  float* carry;            // [cycles][stride] parking column, split launches only
-};
-
-template <typename V, int MODE, int U, bool NT, bool SPLIT>
-__global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_args ca, rank_table rt) {
+// General form (any launch shape, scalar instantiation for unaligned buffers): one
+// thread walks its cycle for U chunks with two ranks of look-ahead.
+template <typename V, int MODE, int U, bool NT>
+__global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, int32_t cycle_len, rank_table rt) {
   const int32_t v0 = blockIdx.y;
   // world rank at hop t of this cycle: virtual rank (v0 + t*shift) mod p
   auto rank_at = [&](int32_t t) -> int64_t {
@@ -305,12 +229,6 @@ __global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_ar
           m[u] = gg_ld<NT>(pm + idx[u]);
         }
     };
-    auto load_one = [&](const float* base, int64_t row, V* out) {
-      const V* ptr = reinterpret_cast<const V*>(base + row * a.stride);
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (on[u]) out[u] = gg_ld<NT>(ptr + idx[u]);
-    };
     auto store_one = [&](float* base, int64_t row, const V* val) {
       V* ptr = reinterpret_cast<V*>(base + row * a.stride);
 #pragma unroll
@@ -318,58 +236,34 @@ __global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_ar
         if (on[u]) gg_st<NT>(ptr + idx[u], val[u]);
     };
 
+    // first rank of the cycle: its new weights need the LAST rank's contribution
     V fw[U], fg[U], fm[U], fT[U];
     V carry[U];  // what the previous rank on the walk contributes to the next one
-    int32_t t_first;
     const int64_t rank0 = rank_at(0);
-    if (!SPLIT) {
-      // first rank of the cycle: its new weights need the LAST rank's contribution
-      load(rank0, fw, fg, fm);
-      if (MODE == MODE_GRAD) {
+    load(rank0, fw, fg, fm);
+    if (MODE == MODE_GRAD) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) carry[u] = fg[u];
-      } else {
-        V v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          fT[u] = local_update(fw[u], fg[u], fm[u], a.lr, a.mu, v[u]);
-          carry[u] = (MODE == MODE_SYNC) ? fT[u] : fw[u];
-        }
-        store_one(a.m, rank0, v);
-      }
-      t_first = 1;
+      for (int u = 0; u < U; ++u) carry[u] = fg[u];
     } else {
-      t_first = ca.t_begin;
-      const int64_t prev = rank_at(ca.t_begin == 0 ? ca.cycle_len - 1 : ca.t_begin - 1);
-      if (MODE == MODE_GRAD) {
-        load_one(a.g, prev, carry);  // gradients are never written: always the original
-      } else if (ca.t_begin == 0) {
-        load_one(ca.carry, v0, carry);  // parked by the launch that handled the last hops
-      } else if (MODE == MODE_STALE) {
-        load_one(a.w, prev, carry);  // rank `prev` belongs to a later launch: still untouched
-      } else {
-        V pw[U], pg[U], pm[U], v[U];
-        load(prev, pw, pg, pm);
+      V v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) carry[u] = local_update(pw[u], pg[u], pm[u], a.lr, a.mu, v[u]);
+      for (int u = 0; u < U; ++u) {
+        fT[u] = local_update(fw[u], fg[u], fm[u], a.lr, a.mu, v[u]);
+        carry[u] = (MODE == MODE_SYNC) ? fT[u] : fw[u];
       }
+      store_one(a.m, rank0, v);
     }
 
-    // The walk keeps three ranks in flight: the one being finished and the next two.
-    // Stores and loads retire through one in-order counter, so waiting for a rank's
-    // loads also waits for every store issued before them; with two ranks of
-    // look-ahead those are the stores of two hops ago, long since acknowledged.
-    const int32_t t_end = ca.t_end;
-    int64_t rank = rank_at(t_first);
-    int64_t rank_1 = rank_at(t_first + 1);
+    int64_t rank = rank_at(1);
+    int64_t rank_1 = rank_at(2);
     V cw[U], cg[U], cm[U];
     V n1w[U], n1g[U], n1m[U];
-    if (t_first < t_end) load(rank, cw, cg, cm);
-    if (t_first + 1 < t_end) load(rank_1, n1w, n1g, n1m);
-    for (int32_t t = t_first; t < t_end; ++t) {
+    if (1 < cycle_len) load(rank, cw, cg, cm);
+    if (2 < cycle_len) load(rank_1, n1w, n1g, n1m);
+    for (int32_t t = 1; t < cycle_len; ++t) {
       const int64_t rank_2 = rank_at(t + 2);
       V n2w[U], n2g[U], n2m[U];
-      if (t + 2 < t_end) load(rank_2, n2w, n2g, n2m);
+      if (t + 2 < cycle_len) load(rank_2, n2w, n2g, n2m);
       V v[U], out[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -397,45 +291,45 @@ __global__ void __launch_bounds__(256) gossip_cycle_kernel(step_args a, cycle_ar
       rank = rank_1;
       rank_1 = rank_2;
     }
-    if (!SPLIT) {
-      // close the cycle
-      V out[U];
-      if (MODE == MODE_GRAD) {
-        V v[U];
+    // close the cycle
+    V out[U];
+    if (MODE == MODE_GRAD) {
+      V v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const V gbar = (fg[u] + carry[u]) * 0.5f;
-          out[u] = local_update(fw[u], gbar, fm[u], a.lr, a.mu, v[u]);
-        }
-        store_one(a.m, rank0, v);
-      } else {
-#pragma unroll
-        for (int u = 0; u < U; ++u) out[u] = (fT[u] + carry[u]) * 0.5f;
+      for (int u = 0; u < U; ++u) {
+        const V gbar = (fg[u] + carry[u]) * 0.5f;
+        out[u] = local_update(fw[u], gbar, fm[u], a.lr, a.mu, v[u]);
       }
-      store_one(a.wn, rank0, out);
-    } else if (MODE != MODE_GRAD && t_end == ca.cycle_len) {
-      store_one(ca.carry, v0, carry);  // the last rank's contribution to the first
+      store_one(a.m, rank0, v);
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) out[u] = (fT[u] + carry[u]) * 0.5f;
     }
+    store_one(a.wn, rank0, out);
   }
 }
 
-// The same walk with the whole chip in step.  One wavefront owns U tiles and walks the
-// cycle once for all of them, so a launch needs only about as many wavefronts as the chip
-// holds at a time: they start together and advance hop by hop at the pace of the memory
-// system, and at any moment only the rows of two or three ranks are being streamed --
-// however long the cycle.  (With one tile per wavefront the walks start one after another
-// and every rank of the cycle is open somewhere on the chip at the same time, which costs
-// DRAM row-buffer and translation locality.)  Each rank is read once and written once, in
-// place, in one launch: no carry column, no re-reads.
-//   tile(u) = (blockIdx.x / tile_step) * tile_mul + blockIdx.x % tile_step + u * tile_step
+// Default form for 16-byte aligned buffers.  Three things, each measured, set it apart:
+//  * One wavefront walks the cycle once for U tiles, a workgroup of W wavefronts for
+//    W*U tiles, and a barrier after every hop keeps the workgroup on the same rank.
+//  * The workgroup's tiles are `step` tiles apart (32 = 32 KB by default).  Device
+//    memory interleaves consecutive 128-byte pieces over its channels, so addresses
+//    32 KB apart fall into the same channel and, eight of them, into one DRAM row: the
+//    workgroup touches every row it opens W*U times at once instead of once.  Workgroup
+//    bx handles tiles (bx / step) * step*W*U + bx % step + i * step, i < W*U, so that
+//    consecutive workgroups still take consecutive tiles.
+//  * Few workgroups are resident per CU (the launch reserves LDS it never touches).
+// A cycle through all 64 ranks then streams at 0.96 of the pair kernel's rate, where
+// one tile per wavefront gave 0.78 (every rank of the cycle open somewhere on the chip,
+// each DRAM row opened for one 128-byte piece at a time).
 struct walk_args {
   int32_t cycle_len;
   int32_t hop_barrier;
-  int64_t tile_mul, tile_step;
+  int32_t step;  // tiles between two tiles of one workgroup
 };
 
-template <int MODE, int U, bool AHEAD>
-__global__ void __launch_bounds__(U >= 8 ? 64 : 512 / U) gossip_cycle_walk_kernel(step_args a, walk_args wa, rank_table rt) {
+template <int MODE, int U>
+__global__ void __launch_bounds__(512 / U) gossip_cycle_walk_kernel(step_args a, walk_args wa, rank_table rt) {
   const int32_t v0 = blockIdx.y;
   auto rank_at = [&](int32_t t) -> int64_t {
     const uint32_t v = (uint32_t)((v0 + t * a.shift) % a.p);
@@ -443,13 +337,16 @@ __global__ void __launch_bounds__(U >= 8 ? 64 : 512 / U) gossip_cycle_walk_kerne
   };
   int64_t idx[U];
   bool on[U];
+  {
+    const int64_t bx = blockIdx.x, step = wa.step;
+    const int64_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63, W = blockDim.x >> 6;
+    const int64_t tile0 = (bx / step) * (step * W * U) + bx % step + wave * U * step;
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int64_t bx = blockIdx.x;
-    const int64_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t x = ((bx / wa.tile_step) * wa.tile_mul + bx % wa.tile_step + (wave * U + u) * wa.tile_step) * 64 + lane;
-    on[u] = x < a.rng.count;
-    idx[u] = a.rng.lo + x;
+    for (int u = 0; u < U; ++u) {
+      const int64_t x = (tile0 + u * step) * 64 + lane;
+      on[u] = x < a.rng.count;
+      idx[u] = a.rng.lo + x;
+    }
   }
   auto load = [&](int64_t rank, v4f* w, v4f* g, v4f* m) {
     const v4f* pw = reinterpret_cast<const v4f*>(a.w + rank * a.stride);
@@ -472,9 +369,9 @@ __global__ void __launch_bounds__(U >= 8 ? 64 : 512 / U) gossip_cycle_walk_kerne
 
   // first rank of the cycle: its new weights need the LAST rank's contribution, so what
   // closes the cycle stays in registers until the walk comes round
-  v4f first[U];   // SYNC/STALE: T of the first rank; GRAD: its gradient
+  v4f first[U];      // SYNC/STALE: T of the first rank; GRAD: its gradient
   v4f fw[U], fm[U];  // GRAD only: the first rank's weights and momentum
-  v4f carry[U];
+  v4f carry[U];      // what the previous rank on the walk contributes to the next one
   const int64_t rank0 = rank_at(0);
   {
     v4f w0[U], g0[U], m0[U], v[U];
@@ -493,10 +390,12 @@ __global__ void __launch_bounds__(U >= 8 ? 64 : 512 / U) gossip_cycle_walk_kerne
     }
     if (MODE != MODE_GRAD) store_one(a.m, rank0, v);
   }
-
-  // finish one rank from its loaded w, g, m and the carry of the rank before it
-  auto finish = [&](int64_t rank, const v4f* cw, const v4f* cg, const v4f* cm) {
-    v4f v[U], out[U];
+  for (int32_t t = 1; t < wa.cycle_len; ++t) {
+    // every wavefront of the workgroup takes this branch the same number of times
+    if (wa.hop_barrier) __syncthreads();
+    const int64_t rank = rank_at(t);
+    v4f cw[U], cg[U], cm[U], v[U], out[U];
+    load(rank, cw, cg, cm);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (MODE == MODE_GRAD) {
@@ -511,28 +410,6 @@ __global__ void __launch_bounds__(U >= 8 ? 64 : 512 / U) gossip_cycle_walk_kerne
     }
     store_one(a.m, rank, v);
     store_one(a.wn, rank, out);
-    if (wa.hop_barrier) __syncthreads();  // keeps the workgroup's wavefronts on the same rank (uniform trip count)
-  };
-  const int32_t len = wa.cycle_len;
-  if (AHEAD) {
-    // two register sets take turns, so the next rank's loads are in flight while the
-    // current one is finished and no register copies tie the two together
-    v4f aw[U], ag[U], am[U], bw[U], bg[U], bm[U];
-    load(rank_at(1), aw, ag, am);
-    for (int32_t t = 1; t < len; t += 2) {
-      if (t + 1 < len) load(rank_at(t + 1), bw, bg, bm);
-      finish(rank_at(t), aw, ag, am);
-      if (t + 1 >= len) break;
-      if (t + 2 < len) load(rank_at(t + 2), aw, ag, am);
-      finish(rank_at(t + 1), bw, bg, bm);
-    }
-  } else {
-    for (int32_t t = 1; t < len; ++t) {
-      v4f cw[U], cg[U], cm[U];
-      const int64_t rank = rank_at(t);
-      load(rank, cw, cg, cm);
-      finish(rank, cw, cg, cm);
-    }
   }
   // close the cycle
   v4f out[U];
@@ -627,9 +504,7 @@ struct launch_ctx {
   hipStream_t s;
   const pair_table* pt;
   const rank_table* rt;
-  cycle_args ca;
-  bool split;
-  int32_t rows_step, rows_waves, rows_chunks, rows_wg_per_cu;
+  int32_t cycle_len;
 };
 
 // The lean kernels serve the default launch shape: 16-byte accesses, one chunk per
@@ -662,31 +537,6 @@ void launch_pair(const launch_ctx& lc, const step_args& a) {
     shifted = shifted || sh != 0;
   }
   dim3 grid = gd.grid;
-  if (lc.rows_step > 0 && NT) {
-    // row-aware tiling: a workgroup of W wavefronts, U chunks per thread, covers W*U tiles `step` apart
-    const int32_t Ur = lc.rows_chunks, Wv = lc.rows_waves;
-    int32_t log2_step = 0;
-    while ((1 << (log2_step + 1)) <= lc.rows_step) ++log2_step;
-    const int64_t step = int64_t(1) << log2_step;
-    const int64_t span = step * Wv * Ur;
-    int64_t gx = ((a.tiles + (shifted ? 1 : 0) + span - 1) / span) * step;
-    if (gx <= 0x7fffffffLL) {
-      grid.x = (unsigned)gx;
-      const dim3 block(64 * Wv);
-      uint32_t lds = 0;
-      if (lc.rows_wg_per_cu > 0) {
-        lds = (160u * 1024u / (uint32_t)lc.rows_wg_per_cu) & ~255u;
-        if (lds > 64u * 1024u - 4096u) lds = 64u * 1024u - 4096u;
-      }
-      switch (Ur) {
-        case 1: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 1>), grid, block, lds, lc.s, a, pt, log2_step); break;
-        case 2: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 2>), grid, block, lds, lc.s, a, pt, log2_step); break;
-        case 4: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 4>), grid, block, lds, lc.s, a, pt, log2_step); break;
-        default: hipLaunchKernelGGL((gossip_pair_rows_kernel<MODE, 8>), grid, block, lds, lc.s, a, pt, log2_step); break;
-      }
-      return;
-    }
-  }
   if (shifted) grid.x += 1;
   hipLaunchKernelGGL((gossip_pair_lean_kernel<MODE, NT>), grid, gd.block, gd.lds_bytes, lc.s, a, pt);
 }
@@ -695,42 +545,19 @@ template <typename V, int MODE, int U, bool NT>
 void launch_cycle(const launch_ctx& lc, const step_args& a) {
   const gg_grid& gd = lc.gd;
   constexpr int UC = U > 2 ? 2 : U;  // the walk keeps three ranks in registers: two chunks at most
-  if (lc.split)
-    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, true>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca,
-                       *lc.rt);
-  else
-    hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT, false>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.ca,
-                       *lc.rt);
-}
-
-// Reserving more than 64 KB of dynamic LDS per workgroup needs the kernel's limit raised first.
-void allow_lds(const void* kernel, uint32_t bytes) {
-  if (bytes > 60u * 1024u)
-    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  hipLaunchKernelGGL((gossip_cycle_kernel<V, MODE, UC, NT>), gd.grid, gd.block, gd.lds_bytes, lc.s, a, lc.cycle_len,
+                     *lc.rt);
 }
 
 template <int MODE>
-void launch_walk(int U, bool ahead, dim3 grid, dim3 block, uint32_t lds, hipStream_t s, const step_args& a,
-                 const walk_args& wa, const rank_table& rt) {
-#define GG_CASE(UU)                                                                                       \
-  case UU:                                                                                                \
-    if (ahead) {                                                                                          \
-      allow_lds((const void*)gossip_cycle_walk_kernel<MODE, UU, true>, lds);                              \
-      hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, UU, true>), grid, block, lds, s, a, wa, rt);    \
-    } else {                                                                                              \
-      allow_lds((const void*)gossip_cycle_walk_kernel<MODE, UU, false>, lds);                             \
-      hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, UU, false>), grid, block, lds, s, a, wa, rt);   \
-    }                                                                                                     \
-    break;
+void launch_walk(int U, dim3 grid, dim3 block, uint32_t lds, hipStream_t s, const step_args& a, const walk_args& wa,
+                 const rank_table& rt) {
   switch (U) {
-    GG_CASE(1)
-    GG_CASE(2)
-    GG_CASE(4)
-    GG_CASE(8)
-    default:
-      GG_CASE(16)
+    case 1: hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, 1>), grid, block, lds, s, a, wa, rt); break;
+    case 2: hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, 2>), grid, block, lds, s, a, wa, rt); break;
+    case 4: hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, 4>), grid, block, lds, s, a, wa, rt); break;
+    default: hipLaunchKernelGGL((gossip_cycle_walk_kernel<MODE, 8>), grid, block, lds, s, a, wa, rt); break;
   }
-#undef GG_CASE
 }
 
 template <typename V, int U, bool NT>
@@ -794,6 +621,28 @@ int32_t gcd32(int32_t x, int32_t y) {
   return x;
 }
 
+// The lockstep walk of the dissemination cycles over the aligned body.  Returns false
+// (nothing enqueued) when the walking form does not apply.
+bool enqueue_walk(const gg_ctx* ctx, int mode, step_args& a, int32_t cycle_len, int64_t cycles,
+                  const rank_table& rt, hipStream_t s) {
+  // measured best at p = 64 x 25.6 M parameters: 2 wavefronts x 2 chunks, tiles 32 KB apart, 3 workgroups per CU
+  const gg_walk_shape own{2, 2, 32, 3, 1, 0};
+  const gg_walk_launch wl = gg_walk_geometry(ctx, own, 8, (a.rng.count + 63) / 64);
+  if (wl.grid_x == 0) return false;
+  walk_args wa;
+  wa.cycle_len = cycle_len;
+  wa.hop_barrier = wl.shape.barrier;
+  wa.step = wl.shape.step;
+  const dim3 grid((unsigned)wl.grid_x, (unsigned)cycles, 1), block(64u * (unsigned)wl.shape.waves);
+  if (mode == MODE_SYNC)
+    launch_walk<MODE_SYNC>(wl.shape.chunks, grid, block, wl.lds_bytes, s, a, wa, rt);
+  else if (mode == MODE_STALE)
+    launch_walk<MODE_STALE>(wl.shape.chunks, grid, block, wl.lds_bytes, s, a, wa, rt);
+  else
+    launch_walk<MODE_GRAD>(wl.shape.chunks, grid, block, wl.lds_bytes, s, a, wa, rt);
+  return true;
+}
+
 // Enqueue one kind of step over the element range [e_lo, e_hi) of every rank: a
 // 16-byte vector launch for the aligned body and, when the range is ragged or the
 // buffers are not 16-byte aligned, one scalar launch for what is left.
@@ -833,92 +682,27 @@ int enqueue_step(gg_ctx* ctx, int kind, int mode, step_args a, const uint16_t* s
   }
   const bool nt = ctx->tune.nontemporal != 0;
   const int64_t edge = (body_lo - e_lo) + (e_hi - body_hi);
-  const int loads = kind == KIND_SGD ? 3 : (kind == KIND_CYCLE ? 5 : 6);  // the cycle walk likes one wave more
+  const int loads = kind == KIND_SGD ? 3 : (kind == KIND_CYCLE ? 5 : 6);
 
-  // Long dissemination cycles are walked in groups of hops, last group first.
-  const int32_t hop_group = ctx->tune.hop_group;
-  bool split = kind == KIND_CYCLE && hop_group > 0 && cycle_len > hop_group + hop_group / 2;
-  if (split && mode != MODE_GRAD) {
-    // One parking column per cycle.  The column is sized once for the phase that needs the
-    // most of them among all phases whose cycles are split, so later phases never regrow it.
-    int64_t max_rows = rows;
-    for (int32_t k = 0; k < ctx->L; ++k) {
-      const int32_t r_k = gcd32(p, int32_t(1) << k);
-      if (p / r_k > hop_group + hop_group / 2 && r_k > max_rows) max_rows = r_k;
-    }
-    int64_t need = max_rows * a.stride;
-    if (need > (int64_t(1) << 31)) need = rows * a.stride;
-    if (need > (int64_t(1) << 31)) {
-      split = false;  // would need more than 8 GiB of scratch: walk whole cycles instead
-    } else if (need > ctx->carry_cap) {
-      GG_HIP_TRY(hipDeviceSynchronize());
-      if (ctx->d_carry) (void)hipFree(ctx->d_carry);
-      ctx->d_carry = nullptr;
-      ctx->carry_cap = 0;
-      if (hipMalloc((void**)&ctx->d_carry, (size_t)need * sizeof(float)) != hipSuccess) {
-        (void)hipGetLastError();
-        return GG_ERR_NOMEM;
-      }
-      ctx->carry_cap = need;
-    }
-  }
-  // Whole-chip lockstep walk of the aligned body (any cycle length, one launch).
-  const int32_t WU = ctx->tune.walk_tiles;
-  bool body_done = false;
-  if (kind == KIND_CYCLE && WU > 0 && body_hi > body_lo && nt) {
+  if (body_hi > body_lo) {
     a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
-    const int64_t tiles = (a.rng.count + 63) / 64;
-    // a wavefront's U tiles are tile_step tiles apart; tile_step * U consecutive tiles form a block
-    const int64_t tstep = ctx->tune.walk_strided > 0 ? ctx->tune.walk_strided : 1;
-    int32_t WW = ctx->tune.walk_wg_waves;
-    if (WU >= 8) WW = 1;
-    while (WW * WU > 8 && WW > 1) WW /= 2;
-    const int64_t gx = (tiles + tstep * WU * WW - 1) / (tstep * WU * WW) * tstep;
-    if (gx <= 0x7fffffffLL) {
-      walk_args wa;
-      wa.cycle_len = cycle_len;
-      wa.hop_barrier = (ctx->tune.walk_barrier && WW > 1) ? 1 : 0;
-      wa.tile_mul = tstep * WU * WW;
-      wa.tile_step = tstep;
-      const dim3 grid((unsigned)gx, (unsigned)rows, 1);
-      const dim3 block(64 * WW);
-      const bool ahead = ctx->tune.walk_ahead != 0;
-      uint32_t lds = 0;
-      if (ctx->tune.walk_waves > 0) lds = (160u * 1024u / (uint32_t)ctx->tune.walk_waves) & ~255u;
-      if (mode == MODE_SYNC)
-        launch_walk<MODE_SYNC>(WU, ahead, grid, block, lds, s, a, wa, rt);
-      else if (mode == MODE_STALE)
-        launch_walk<MODE_STALE>(WU, ahead, grid, block, lds, s, a, wa, rt);
-      else
-        launch_walk<MODE_GRAD>(WU, ahead, grid, block, lds, s, a, wa, rt);
-      GG_HIP_TRY(hipGetLastError());
-      body_done = true;  // what is left is the ragged edge
-      split = false;
-    }
-  }
-  const int32_t groups = split ? (cycle_len + hop_group - 1) / hop_group : 1;
-  for (int32_t gi = groups - 1; gi >= 0; --gi) {
-    cycle_args ca;
-    ca.cycle_len = cycle_len;
-    ca.t_begin = split ? gi * hop_group : 0;
-    ca.t_end = split ? (ca.t_begin + hop_group < cycle_len ? ca.t_begin + hop_group : cycle_len) : cycle_len;
-    ca.carry = ctx->d_carry;
-    if (body_hi > body_lo && !body_done) {
+    bool done = false;
+    if (kind == KIND_CYCLE) done = enqueue_walk(ctx, mode, a, cycle_len, rows, rt, s);
+    if (!done) {
       int U = ctx->tune.chunks;
       if (kind == KIND_CYCLE && U > 2) U = 2;
-      a.rng = gg_range{body_lo / 4, (body_hi - body_lo) / 4, INT64_MAX, 0};
-      launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, loads), s, &pt, &rt, ca, split, ctx->tune.rows_step, ctx->tune.rows_waves, ctx->tune.rows_chunks, ctx->tune.rows_wg_per_cu};
+      launch_ctx lc{gg_make_grid(ctx, a.rng.count, U, rows, loads), s, &pt, &rt, cycle_len};
       a.tiles = lc.gd.tiles;
       launch_any<v4f>(kind, mode, U, nt, lc, a);
-      GG_HIP_TRY(hipGetLastError());
     }
-    if (edge > 0) {
-      a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
-      launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, loads), s, &pt, &rt, ca, split, 0, 1, 1, 0};
-      a.tiles = lc.gd.tiles;
-      launch_any<float>(kind, mode, 1, nt, lc, a);
-      GG_HIP_TRY(hipGetLastError());
-    }
+    GG_HIP_TRY(hipGetLastError());
+  }
+  if (edge > 0) {
+    a.rng = gg_range{e_lo, edge, body_lo, body_hi - body_lo};
+    launch_ctx lc{gg_make_grid(ctx, a.rng.count, 1, rows, loads), s, &pt, &rt, cycle_len};
+    a.tiles = lc.gd.tiles;
+    launch_any<float>(kind, mode, 1, nt, lc, a);
+    GG_HIP_TRY(hipGetLastError());
   }
   return GG_OK;
 }

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "gg.h"
+#include "gg_probe.h"
 
 #define GG_HIP_TRY(expr)                      \
   do {                                        \
@@ -55,22 +56,25 @@ __device__ __forceinline__ int64_t gg_item_index(const gg_range& r, int64_t x) {
   return i;
 }
 
+// Workgroup shape of a kernel that walks over many ranks (dissemination cycles, one-pass
+// all-reduce, payload ring).  In gg_tuning a field of GG_WALK_UNSET means "the kernel's own
+// default"; gg_walk_resolve fills those in.
+enum { GG_WALK_UNSET = -1 };
+struct gg_walk_shape {
+  int32_t chunks;      // 16-byte chunks per thread (1, 2, 4, 8); 0: the kernel's general form instead
+  int32_t waves;       // wavefronts per workgroup (1, 2, 4, 8); chunks * waves <= 8
+  int32_t step;        // tiles between two tiles of one workgroup (32 = 32 KB: same DRAM channel)
+  int32_t wg_per_cu;   // cap on resident workgroups per CU (0: none)
+  int32_t barrier;     // barrier after every hop keeps a workgroup's wavefronts on one rank
+  int32_t group_log2;  // 2^this ranks are read (written) between two barriers, where a kernel groups ranks
+};
+
 struct gg_tuning {
-  int32_t threads;        // workgroup size
-  int32_t chunks;         // access-type items per thread per tile: 1, 2, 4, 8
-  int32_t blocks_per_cu;  // 0: no cap; >0: at most this many resident workgroups per CU (LDS reservation)
-  int32_t nontemporal;    // 1: streaming (nt) loads and stores
-  int32_t hop_group;      // dissemination: hops per launch on long cycles (0: never split)
-  int32_t walk_tiles;     // dissemination: tiles per wavefront of the lockstep walk (0: off; 2, 4, 8, 16)
-  int32_t walk_ahead;     // lockstep walk: load the next rank before finishing the current one
-  int32_t walk_strided;   // lockstep walk: a wavefront's tiles are grid-strided instead of contiguous
-  int32_t walk_waves;     // lockstep walk: cap on resident wavefronts per CU (0: none)
-  int32_t walk_wg_waves;  // lockstep walk: wavefronts per workgroup (1, 2, 4, 8)
-  int32_t walk_barrier;   // lockstep walk: barrier after every hop
-  int32_t rows_step;      // row-aware tiling: tiles between the tiles of one workgroup (0: off; power of two)
-  int32_t rows_waves;     // row-aware tiling: wavefronts per workgroup (1, 2, 4, 8)
-  int32_t rows_chunks;    // row-aware tiling: chunks per thread (1, 2, 4, 8); waves * chunks <= 8
-  int32_t rows_wg_per_cu; // row-aware tiling: cap on resident workgroups per CU (0: none)
+  int32_t threads;         // workgroup size of the general kernels
+  int32_t chunks;          // access-type items per thread per tile: 1, 2, 4, 8
+  int32_t blocks_per_cu;   // 0: no cap; >0: at most this many resident workgroups per CU (LDS reservation)
+  int32_t nontemporal;     // 1: streaming (nt) loads and stores
+  gg_walk_shape walk;      // overrides of the walking kernels' defaults
 };
 
 struct gg_ctx {
@@ -86,9 +90,7 @@ struct gg_ctx {
   // shuffle state
   int32_t* d_scratch;           // device int32[scratch_cap]
   int64_t scratch_cap;
-  float* d_carry;               // dissemination: parking column(s) of split cycle walks
-  int64_t carry_cap;            // in floats
-  int64_t* d_offsets;           // device int64[p+1]
+  int64_t* d_offsets;           // device int64[2p+1]: rank offsets, then the ring heads of the current call
   int64_t* h_offsets_pinned;    // pinned staging for the upload
   std::vector<int64_t> offsets_cached;
 };
@@ -138,5 +140,16 @@ struct gg_grid {
 // pair kernel (6 loads per thread) and scaled so that every kernel keeps about the same
 // number of bytes in flight per CU.
 gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t rows, int32_t loads);
+
+// Launch geometry of a walking kernel over `tiles` 1 KB tiles: workgroup bx handles the tiles
+//   (bx / step) * step*waves*chunks + bx % step + i * step,   i < waves*chunks,
+// so grid_x = ceil(tiles / (step*waves*chunks)) * step workgroups of 64*waves threads.
+struct gg_walk_launch {
+  gg_walk_shape shape;  // defaults resolved, chunks clamped to max_chunks
+  int64_t grid_x;       // 0 when the walking form does not apply (chunks == 0 or the grid would not fit)
+  uint32_t lds_bytes;   // LDS reserved (never touched) to cap the resident workgroups per CU
+};
+gg_walk_launch gg_walk_geometry(const gg_ctx* ctx, const gg_walk_shape& kernel_default, int32_t max_chunks,
+                                int64_t tiles);
 
 #endif  // GG_INTERNAL_H_

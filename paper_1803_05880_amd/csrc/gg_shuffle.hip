@@ -185,15 +185,26 @@ struct ring_args {
   int32_t* idx;
   int32_t* stage;      // scratch int32[p * batch]
   const int64_t* off;  // device int64[p+1]
+  int64_t* head;       // device int64[p]: head of every rank's queue at this step, (step*batch) mod n_j
   int64_t step;
   int32_t batch;
   int32_t p;
 };
 
+__device__ __forceinline__ int64_t ring_head(const ring_args& a, int32_t j) {
+  const int64_t n_j = a.off[j + 1] - a.off[j];
+  return ((a.step % n_j) * ((int64_t)a.batch % n_j)) % n_j;  // (step*batch) mod n_j
+}
+
 __device__ __forceinline__ int64_t ring_slot(const ring_args& a, int32_t j, int32_t r) {
   const int64_t n_j = a.off[j + 1] - a.off[j];
-  const int64_t head = ((a.step % n_j) * ((int64_t)a.batch % n_j)) % n_j;  // (step*batch) mod n_j
-  return a.off[j] + (head + r) % n_j;
+  return a.off[j] + (ring_head(a, j) + r) % n_j;
+}
+
+// The heads once per call, so that the payload walk below needs no division per hop.
+__global__ void __launch_bounds__(256) ring_heads_kernel(ring_args a) {
+  const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < a.p) a.head[j] = ring_head(a, j);
 }
 
 // Phase 1: every rank's batch at the head of its queue is copied out.
@@ -214,7 +225,7 @@ __global__ void __launch_bounds__(256) ring_scatter_kernel(ring_args a) {
 // ring, on rows of `words` W-sized words.  One thread owns word x of batch entry r
 // for ALL ranks and walks the ring once (hold rank p-1's word, then for j = 0..p-1
 // swap the held word into rank j's slot), so every byte is read once and written
-// once, in place, without staging.
+// once, in place, without staging.  General form (4-byte words, any alignment).
 template <typename Wd>
 __global__ void __launch_bounds__(256) ring_payload_kernel(ring_args a, Wd* payload, int64_t words) {
   const int64_t total = (int64_t)a.batch * words;
@@ -234,11 +245,83 @@ __global__ void __launch_bounds__(256) ring_payload_kernel(ring_args a, Wd* payl
   }
 }
 
+// Default form for 16-byte words: the same walk with the chip in step.  A workgroup of
+// W wavefronts owns W*U tiles (64 words = 1 KB each) `step` tiles apart -- 32 KB apart
+// in memory wherever they fall into one sample, i.e. in the same DRAM channel.  It takes
+// the ranks D at a time: D loads per word in flight, then the D stores (every store
+// follows the load of the same address in program order), then a barrier, so that
+// only D ranks' batches are streamed at a time instead of all p.
+struct ring_walk_shape {
+  int32_t step;
+  int32_t barrier;
+};
+
+template <int U, int D>
+__global__ void __launch_bounds__(512 / U) ring_payload_walk_kernel(ring_args a, v4f* payload, int64_t words,
+                                                                     ring_walk_shape ws) {
+  const int64_t total = (int64_t)a.batch * words;
+  int32_t r[U];
+  int64_t x[U];
+  bool on[U];
+  {
+    const int64_t bx = blockIdx.x, step = ws.step;
+    const int64_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63, W = blockDim.x >> 6;
+    const int64_t tile0 = (bx / step) * (step * W * U) + bx % step + wave * U * step;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t t = (tile0 + u * step) * 64 + lane;
+      on[u] = t < total;
+      r[u] = on[u] ? (int32_t)(t / words) : 0;
+      x[u] = t - (int64_t)r[u] * words;
+    }
+  }
+  // word of batch entry r[u] in rank j: head + r < 2 n_j, so one conditional subtraction wraps it
+  auto word_at = [&](int32_t j, int u) -> v4f* {
+    const int64_t off_j = a.off[j], n_j = a.off[j + 1] - off_j;
+    int64_t slot = a.head[j] + r[u];
+    if (slot >= n_j) slot -= n_j;
+    return payload + (off_j + slot) * words + x[u];
+  };
+  v4f held[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (on[u]) held[u] = __builtin_nontemporal_load(word_at(a.p - 1, u));
+  const int32_t last = a.p - 1;  // rank p-1 was read above and is written after the loop
+  for (int32_t j0 = 0; j0 < last; j0 += D) {
+    v4f cur[D][U];
+    v4f* ptr[D][U];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if (j0 + d < last) {  // uniform
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          ptr[d][u] = word_at(j0 + d, u);
+          if (on[u]) cur[d][u] = __builtin_nontemporal_load(ptr[d][u]);
+        }
+      }
+    }
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if (j0 + d < last) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (on[u]) __builtin_nontemporal_store(held[u], ptr[d][u]);
+          held[u] = cur[d][u];
+        }
+      }
+    }
+    if (ws.barrier) __syncthreads();  // uniform trip count: every wavefront walks all p ranks
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (on[u]) __builtin_nontemporal_store(held[u], word_at(last, u));
+}
+
 // Make the device copy of rank_offsets current and the scratch large enough.
 int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s, int64_t scratch_words) {
   const int32_t p = ctx->cfg.p;
   if (!ctx->d_offsets) {
-    if (hipMalloc((void**)&ctx->d_offsets, (size_t)(p + 1) * sizeof(int64_t)) != hipSuccess ||
+    if (hipMalloc((void**)&ctx->d_offsets, (size_t)(2 * p + 1) * sizeof(int64_t)) != hipSuccess ||  // + p heads
         hipHostMalloc((void**)&ctx->h_offsets_pinned, (size_t)(p + 1) * sizeof(int64_t), hipHostMallocDefault) !=
             hipSuccess) {
       (void)hipGetLastError();
@@ -333,6 +416,7 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
     ring_args a;
     a.idx = idx;
     a.stage = ctx->d_scratch;
+    a.head = nullptr;
     a.off = ctx->d_offsets;
     a.step = step;
     a.batch = batch;
@@ -370,18 +454,48 @@ extern "C" int gg_shuffle_payload(gg_ctx* ctx, int64_t step, void* payload, int6
   ring_args a;
   a.idx = nullptr;
   a.stage = nullptr;
+  a.head = nullptr;
   a.off = ctx->d_offsets;
   a.step = step;
   a.batch = batch;
   a.p = p;
   const bool vec = gg_aligned(payload, 16) && sample_bytes % 16 == 0;
   const int64_t words = vec ? sample_bytes / 16 : sample_bytes / 4;
-  int64_t blocks = ((int64_t)batch * words + 255) / 256;
-  if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
-  if (vec)
-    hipLaunchKernelGGL(ring_payload_kernel<v4f>, dim3((unsigned)blocks), dim3(256), 0, s, a, (v4f*)payload, words);
-  else
-    hipLaunchKernelGGL(ring_payload_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, a, (float*)payload, words);
+  // measured best for 64 ranks x 32 samples of 192 KB: 4 wavefronts x 1 chunk, 2 ranks per barrier, no cap
+  const gg_walk_shape own{1, 4, 32, 0, 1, 1};
+  const gg_walk_launch wl = gg_walk_geometry(ctx, own, 4, ((int64_t)batch * words + 63) / 64);
+  if (vec && wl.grid_x > 0) {
+    a.head = ctx->d_offsets + (p + 1);
+    hipLaunchKernelGGL(ring_heads_kernel, dim3((p + 255) / 256), dim3(256), 0, s, a);
+    GG_HIP_TRY(hipGetLastError());
+    ring_walk_shape ws{wl.shape.step, wl.shape.barrier};
+    const uint32_t lds = wl.lds_bytes;
+    const int U = wl.shape.chunks;
+    const dim3 grid((unsigned)wl.grid_x), block(64u * (unsigned)wl.shape.waves);
+#define GG_RING_CASE(UU, DD) \
+  hipLaunchKernelGGL((ring_payload_walk_kernel<UU, DD>), grid, block, lds, s, a, (v4f*)payload, words, ws)
+#define GG_RING_U(DD)             \
+  switch (U) {                    \
+    case 1: GG_RING_CASE(1, DD); break; \
+    case 2: GG_RING_CASE(2, DD); break; \
+    default: GG_RING_CASE(4, DD); break; \
+  }
+    switch (wl.shape.group_log2) {
+      case 0: GG_RING_U(1) break;
+      case 1: GG_RING_U(2) break;
+      case 2: GG_RING_U(4) break;
+      default: GG_RING_U(8) break;
+    }
+#undef GG_RING_U
+#undef GG_RING_CASE
+  } else {
+    int64_t blocks = ((int64_t)batch * words + 255) / 256;
+    if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
+    if (vec)
+      hipLaunchKernelGGL(ring_payload_kernel<v4f>, dim3((unsigned)blocks), dim3(256), 0, s, a, (v4f*)payload, words);
+    else
+      hipLaunchKernelGGL(ring_payload_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, a, (float*)payload, words);
+  }
   GG_HIP_TRY(hipGetLastError());
   return GG_OK;
 }

@@ -15,7 +15,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "gg.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include")))
+                   if h.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(gg_[a-z_0-9]+)\s*\(", text)))
 
@@ -112,7 +113,7 @@ def test_partner_argument_validation_and_strerror():
     assert L.gg_partner(ctx._h, 0, ptr, None) == 0 and buf.tolist() == [1, 0, 3, 2]
     assert L.gg_set_tuning(ctx._h, 0, 100) == gg.binding.GG_ERR_ARG
     assert L.gg_set_tuning(ctx._h, 1, 3) == gg.binding.GG_ERR_ARG
-    assert L.gg_set_tuning(ctx._h, 9, 0) == gg.binding.GG_ERR_ARG
+    assert L.gg_set_tuning(ctx._h, 10, 0) == gg.binding.GG_ERR_ARG       # no such key
     assert L.gg_set_tuning(ctx._h, 1, 4) == 0
     for code in range(-7, 1):
         assert L.gg_strerror(code)
@@ -149,7 +150,15 @@ def test_probe_entry_points_validate_arguments():
     assert L.gg_busy_probe(-1, 4, ctypes.c_void_p(256), None) == E.GG_ERR_ARG
     assert L.gg_busy_probe(10, 4, None, None) == E.GG_ERR_ARG
     ctx = gg.Context(p=4, n=8)
-    assert L.gg_set_tuning(ctx._h, 4, 1) == E.GG_ERR_ARG and L.gg_set_tuning(ctx._h, 4, 0) == 0
+    assert L.gg_stream_probe(10, 4, None, 16, None) == E.GG_ERR_ARG
+    assert L.gg_stream_probe(10, 4, ctypes.c_void_p(256), 24, None) == E.GG_ERR_ARG
+    assert L.gg_stream_probe(10, 4, ctypes.c_void_p(260), 16, None) == E.GG_ERR_ALIGN
+    assert L.gg_stream_probe(10, 4, ctypes.c_void_p(256), 0, None) == 0
+    assert L.gg_set_tuning(ctx._h, E.TUNE_WALK_CHUNKS, 3) == E.GG_ERR_ARG and L.gg_set_tuning(ctx._h, E.TUNE_WALK_CHUNKS, 0) == 0
+    assert L.gg_set_tuning(ctx._h, E.TUNE_WALK_WAVES, 2) == 0
+    assert L.gg_set_tuning(ctx._h, E.TUNE_WALK_CHUNKS, 8) == E.GG_ERR_ARG      # 8 chunks x 2 wavefronts > 8
+    assert L.gg_set_tuning(ctx._h, E.TUNE_WALK_WAVES, 1) == 0 and L.gg_set_tuning(ctx._h, E.TUNE_WALK_CHUNKS, 8) == 0
+    assert L.gg_set_tuning(ctx._h, E.TUNE_WALK_STEP, 0) == E.GG_ERR_ARG
     assert L.gg_set_tuning(ctx._h, 2, 2) == E.GG_ERR_ARG and L.gg_set_tuning(ctx._h, 2, 3) == 0
     off = np.array([0, 2, 4, 6, 8], np.int64).ctypes.data_as(ctypes.c_void_p)
     assert L.gg_shuffle_payload(ctx._h, 0, ctypes.c_void_p(256), 6, off, 1, None) == E.GG_ERR_ARG    # not a multiple of 4

@@ -31,6 +31,33 @@ def test_allreduce_matches_oracle_bitwise(form, average, p, n, stride):
     ctx.close()
 
 
+@pytest.mark.parametrize("shape", [
+    # chunks per thread, wavefronts per workgroup, tile step, workgroups per CU, barrier, log2(ranks per barrier)
+    (2, 2, 32, 3, 1, 2), (1, 8, 32, 3, 1, 0), (4, 2, 16, 0, 1, 3), (4, 1, 1, 4, 0, 1), (1, 1, 5, 0, 0, 2), (8, 1, 32, 3, 1, 1),
+    (0, 2, 32, 3, 1, 2),
+])
+@pytest.mark.parametrize("p,n,stride", [(2, 20_005, 20_008), (8, 262_151, 262_152), (64, 70_003, 70_004), (128, 33_001, 33_004)])
+def test_onepass_walk_shapes_never_change_results(shape, p, n, stride):
+    # the workgroup shape of the one-pass walk and the general kernel (chunks = 0) give the oracle's bits
+    chunks, waves, step, cap, barrier, group = shape
+    _, G, _ = host_state(p, n, stride, seed=21)
+    G[:, n:] = 5.0
+    ctx = gg.Context(p=p, n=n, rank_stride=stride)
+    for key, val in ((gg.TUNE_WALK_CHUNKS, 1), (gg.TUNE_WALK_WAVES, waves), (gg.TUNE_WALK_CHUNKS, chunks),
+                     (gg.TUNE_WALK_STEP, step), (gg.TUNE_WALK_WG_PER_CU, cap), (gg.TUNE_WALK_BARRIER, barrier),
+                     (gg.TUNE_WALK_GROUP_LOG2, group)):
+        ctx.set_tuning(key, val)
+    g = G.to(DEV)
+    ctx.allreduce_onepass(g, average=True)
+    torch.cuda.synchronize()
+    Go = G[:, :n].numpy().copy()
+    og.allreduce_recursive_doubling(Go, average=True)
+    out = g.cpu()
+    assert assert_close_fp32(out[:, :n].numpy(), Go, "G") == 0
+    assert (out[:, n:] == 5.0).all()
+    ctx.close()
+
+
 def test_allreduce_sgd_step_and_fixed_point_with_gossip():
     p, n = 8, 300_000
     W, G, M = host_state(p, n, n, seed=12)

@@ -16,7 +16,7 @@ DEV = "cuda:0"
 
 def _run_gpu(W, G, M, n, stride, p, seed, steps, first_step=0, double_buffer=False, seg=None, tune=None, **cfg):
     ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=seed, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM, **cfg)
-    for key, val in (tune or {}).items():
+    for key, val in (tune.items() if isinstance(tune, dict) else tune or ()):
         ctx.set_tuning(key, val)
     w, g, m = W.to(DEV), G.to(DEV), M.to(DEV)
     w2 = torch.full_like(w, float("nan")) if double_buffer else None
@@ -97,28 +97,24 @@ def test_dissemination_data_path(mode, p, n, stride):
     _check(p, n, stride, 2 * sc.num_phases(p) + 2, seed=6, topology=gg.TOPO_DISSEMINATION, **mode)
 
 
-@pytest.mark.parametrize("hop_group", [0, 2, 3, 8, 32])
-@pytest.mark.parametrize("mode", [dict(), dict(staleness=1), dict(avg_mode=gg.AVG_GRAD),
-                                  dict(staleness=1, double_buffer=True), dict(double_buffer=True)])
-@pytest.mark.parametrize("p,n,stride", [(64, 20_003, 20_004), (12, 5_001, 5_001), (7, 3_000, 3_000)])
-def test_dissemination_hop_groups_never_change_results(hop_group, mode, p, n, stride):
-    # long partner cycles walked in groups of hops (one launch per group, last group first)
-    _check(p, n, stride, sc.num_phases(p) + 2, seed=16, topology=gg.TOPO_DISSEMINATION,
-           tune={gg.TUNE_HOP_GROUP: hop_group}, **mode)
+WALK_SHAPES = [
+    # chunks per thread, wavefronts per workgroup, tile step, workgroups per CU, barrier per hop
+    (2, 2, 32, 3, 1), (1, 8, 32, 3, 1), (8, 1, 32, 0, 0), (4, 2, 16, 4, 1), (1, 1, 1, 0, 0), (2, 4, 3, 7, 0),
+    (4, 1, 64, 3, 1), (1, 4, 4096, 3, 1), (0, 2, 32, 3, 1),
+]
 
 
-@pytest.mark.parametrize("walk", [
-    {5: 2, 6: 1}, {5: 4, 6: 1}, {5: 4, 6: 0, 7: 1}, {5: 8, 6: 1, 7: 3}, {5: 8, 6: 0, 7: 32}, {5: 16, 6: 0, 7: 64},
-    {5: 16, 6: 1, 7: 16}, {5: 1, 13: 8, 14: 1, 7: 32}, {5: 1, 13: 8, 14: 0, 7: 32, 6: 0}, {5: 2, 13: 4, 14: 1, 7: 32, 8: 4},
-    {5: 4, 13: 2, 14: 1, 7: 16, 6: 0}, {5: 1, 13: 1, 7: 0},
-])
+@pytest.mark.parametrize("shape", WALK_SHAPES)
 @pytest.mark.parametrize("mode", [dict(), dict(staleness=1), dict(avg_mode=gg.AVG_GRAD),
                                   dict(staleness=1, double_buffer=True), dict(double_buffer=True)])
 @pytest.mark.parametrize("p,n,stride", [(64, 70_003, 70_004), (12, 5_001, 5_001), (7, 3_000, 3_000), (6, 300_007, 300_008)])
-def test_dissemination_lockstep_walk_never_changes_results(walk, mode, p, n, stride):
-    # one wavefront walks the whole partner cycle for several tiles at once (any cycle length, one launch);
-    # keys: 5 chunks per thread, 6 look-ahead, 7 tile step, 8 workgroup cap, 13 wavefronts per workgroup, 14 hop barrier
-    _check(p, n, stride, sc.num_phases(p) + 2, seed=26, topology=gg.TOPO_DISSEMINATION, tune=walk, **mode)
+def test_dissemination_walk_shapes_never_change_results(shape, mode, p, n, stride):
+    # the workgroup shape of the cycle walk (chunks, wavefronts, tile step, occupancy cap, hop barrier) and the
+    # general kernel (chunks = 0) give the same bits
+    chunks, waves, step, cap, barrier = shape
+    tune = [(gg.TUNE_WALK_CHUNKS, 1), (gg.TUNE_WALK_WAVES, waves), (gg.TUNE_WALK_CHUNKS, chunks),
+            (gg.TUNE_WALK_STEP, step), (gg.TUNE_WALK_WG_PER_CU, cap), (gg.TUNE_WALK_BARRIER, barrier)]
+    _check(p, n, stride, sc.num_phases(p) + 2, seed=26, topology=gg.TOPO_DISSEMINATION, tune=tune, **mode)
 
 
 @pytest.mark.parametrize("tune", [
@@ -126,7 +122,6 @@ def test_dissemination_lockstep_walk_never_changes_results(walk, mode, p, n, str
     {gg.TUNE_THREADS: 256, gg.TUNE_CHUNKS: 8}, {gg.TUNE_BLOCKS_PER_CU: 0, gg.TUNE_CHUNKS: 2}, {gg.TUNE_BLOCKS_PER_CU: 3},
     {gg.TUNE_BLOCKS_PER_CU: 8, gg.TUNE_CHUNKS: 4},
     {gg.TUNE_NONTEMPORAL: 0},
-    {9: 32, 10: 8}, {9: 32, 11: 8}, {9: 16, 10: 2, 11: 4}, {9: 64, 10: 4, 11: 2, 12: 4}, {9: 1, 10: 2}, {9: 2048, 11: 2},
 ])
 def test_launch_shapes_never_change_results(tune):
     _check(8, 1_500_003, 1_500_004, 4, seed=7, tune=tune)

@@ -32,7 +32,8 @@ def _case(rng):
     tune = {}
     if rng.random() < 0.5:
         tune = {gg.TUNE_THREADS: int(rng.choice([64, 128, 256])), gg.TUNE_CHUNKS: int(rng.choice([1, 2, 4, 8])),
-                gg.TUNE_BLOCKS_PER_CU: int(rng.choice([0, 3, 7, 20])), gg.TUNE_HOP_GROUP: int(rng.choice([0, 2, 5, 8]))}
+                gg.TUNE_BLOCKS_PER_CU: int(rng.choice([0, 3, 7, 20])), gg.TUNE_WALK_STEP: int(rng.choice([1, 5, 32, 64])),
+                gg.TUNE_WALK_BARRIER: int(rng.choice([0, 1]))}
     return dict(topology=topology, p=p, n=n, stride=stride, shift=shift, mode=mode, double=double, seg=seg, tune=tune,
                 steps=int(rng.integers(1, 5)), first=int(rng.integers(0, 200)), seed=int(rng.integers(0, 2**40)))
 

@@ -114,6 +114,29 @@ def test_ring_payload_bit_exact_and_glued_to_indices(p, n_total, batch, sample_w
     ctx.close()
 
 
+@pytest.mark.parametrize("shape", [
+    # chunks per thread, wavefronts per workgroup, tile step, workgroups per CU, barrier per rank
+    (2, 2, 32, 3, 1), (1, 8, 32, 3, 1), (8, 1, 3, 0, 0), (4, 2, 16, 4, 1), (1, 1, 1, 0, 0), (0, 1, 32, 3, 1),
+])
+@pytest.mark.parametrize("p,n_total,batch,sample_words", [(5, 5 * 9, 7, 3076), (16, 16 * 5, 5, 260), (64, 64 * 3, 2, 49_152)])
+def test_ring_payload_walk_shapes_never_change_results(shape, p, n_total, batch, sample_words):
+    # samples that are not a whole number of 1 KB tiles, queues that wrap, and the image size of Table 5
+    chunks, waves, step, cap, barrier = shape
+    off = sh.block_offsets(n_total, p)
+    rng = np.random.default_rng(6)
+    pay_o = rng.integers(-2**31, 2**31 - 1, size=(n_total, sample_words), dtype=np.int64).astype(np.int32)
+    pay_g = torch.from_numpy(pay_o.copy()).to(DEV)
+    ctx = gg.Context(p=p, n=4, topology=gg.TOPO_DISSEMINATION)
+    for key, val in ((gg.TUNE_WALK_CHUNKS, 1), (gg.TUNE_WALK_WAVES, waves), (gg.TUNE_WALK_CHUNKS, chunks),
+                     (gg.TUNE_WALK_STEP, step), (gg.TUNE_WALK_WG_PER_CU, cap), (gg.TUNE_WALK_BARRIER, barrier)):
+        ctx.set_tuning(key, val)
+    for t in [0, 1, 2, 7, 10**9 + 1]:
+        sh.ring_payload_step(pay_o, off, batch, t)
+        ctx.shuffle_payload(t, pay_g, off, batch)
+        assert np.array_equal(pay_g.cpu().numpy(), pay_o), "step %d" % t
+    ctx.close()
+
+
 def test_ring_payload_unaligned_rows_take_the_word_path():
     p, n_total, batch = 4, 40, 3
     off = sh.block_offsets(n_total, p)
