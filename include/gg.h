@@ -54,7 +54,8 @@ typedef enum {
   GG_ERR_ALIGN = -3,    /* a device pointer is not 4-byte aligned                   */
   GG_ERR_HIP = -4,      /* a HIP runtime call failed (launch, copy)                 */
   GG_ERR_NOMEM = -5,    /* host or device allocation failed                         */
-  GG_ERR_UNSUPPORTED = -6 /* valid request this build does not implement            */
+  GG_ERR_UNSUPPORTED = -6, /* valid request this build does not implement           */
+  GG_ERR_LIMIT = -7     /* sizes beyond the fixed scratch of gg_shuffle_noalloc     */
 } gg_status;
 
 enum { GG_TOPO_HYPERCUBE = 0, GG_TOPO_DISSEMINATION = 1 };
@@ -159,6 +160,22 @@ int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void* stream);
  * therefore synchronise the device on the first call or when the offsets change. */
 int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
                const int64_t* rank_offsets, int32_t batch, void* stream);
+
+/* gg_shuffle for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result, same
+ * kernels, but the scratch (rank offsets, flagged-slot lists, per-tile counts, staged
+ * ring batches) is a fixed array that is part of the library image -- one copy per GPU,
+ * about 8.3 MiB, held until the process ends -- and the rank offsets reach the device
+ * in kernel arguments.  The call allocates nothing, frees nothing, copies nothing and
+ * never synchronises.  Limits: rank_offsets[p] <= GG_NOALLOC_MAX_INDICES and
+ * p * ceil(max n_j / 4096) <= GG_NOALLOC_MAX_TILE_COUNTS, else GG_ERR_LIMIT (nothing
+ * enqueued).  Every call on a GPU, from any context, uses that GPU's one array and
+ * overwrites what the last call left: calls that overlap on one GPU race, so order
+ * them (one stream, or events).  Nothing in the array has to be cleared between calls. */
+#define GG_NOALLOC_MAX_INDICES 2097152
+#define GG_NOALLOC_MAX_TILE_COUNTS 65536
+int gg_shuffle_noalloc(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
+                       const int64_t* rank_offsets, int32_t batch, void* stream);
 
 /* The ring rotation of gg_shuffle(GG_SHUF_RING) applied to the samples themselves
  * (Sec. 4.5.2: a rank sends the batch it has just used to its ring neighbour;

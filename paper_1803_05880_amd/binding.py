@@ -16,7 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgg.so")
 
 GG_OK = 0
-GG_ERR_ARG, GG_ERR_NOT_POW2, GG_ERR_ALIGN, GG_ERR_HIP, GG_ERR_NOMEM, GG_ERR_UNSUPPORTED = -1, -2, -3, -4, -5, -6
+GG_ERR_ARG, GG_ERR_NOT_POW2, GG_ERR_ALIGN, GG_ERR_HIP, GG_ERR_NOMEM, GG_ERR_UNSUPPORTED, GG_ERR_LIMIT = -1, -2, -3, -4, -5, -6, -7
+NOALLOC_MAX_INDICES, NOALLOC_MAX_TILE_COUNTS = 2_097_152, 65_536
 TOPO_HYPERCUBE, TOPO_DISSEMINATION = 0, 1
 AVG_MODEL, AVG_GRAD, AVG_NONE = 0, 1, 2
 SHUF_PARTNER_SWAP, SHUF_RING = 0, 1
@@ -81,6 +82,7 @@ def lib():
         L.gg_allreduce_baseline.argtypes = [vp, vp, i32, vp]
         L.gg_allreduce_onepass.argtypes = [vp, vp, i32, vp]
         L.gg_shuffle.argtypes = [vp, i64, i32, vp, vp, i32, vp]
+        L.gg_shuffle_noalloc.argtypes = [vp, i64, i32, vp, vp, i32, vp]
         L.gg_shuffle_payload.argtypes = [vp, i64, vp, i64, vp, i32, vp]
         L.gg_copy_probe.argtypes = [vp, vp, i64, vp]
         L.gg_busy_probe.argtypes = [i64, i32, vp, vp]
@@ -89,7 +91,7 @@ def lib():
         L.gg_strerror.argtypes = [ctypes.c_int]
         L.gg_strerror.restype = ctypes.c_char_p
         for name in ("gg_init", "gg_destroy", "gg_set_hyper", "gg_partner", "gg_gossip_step", "gg_sgd_step",
-                     "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_shuffle_payload", "gg_copy_probe",
+                     "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_shuffle_noalloc", "gg_shuffle_payload", "gg_copy_probe",
                      "gg_busy_probe", "gg_stream_probe", "gg_set_tuning"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -186,6 +188,15 @@ class Context:
             raise ValueError("rank_offsets must have p+1 entries")
         _check(lib().gg_shuffle(self._h, step, mode, _dev_ptr(idx, torch.int32, "idx"),
                                 off.ctypes.data_as(ctypes.c_void_p), batch, _stream_ptr(stream)), "gg_shuffle")
+
+    def shuffle_noalloc(self, step, mode, idx, rank_offsets, batch=0, stream=None):
+        """gg_shuffle_noalloc: gg_shuffle on the library's fixed scratch (allocates nothing)."""
+        off = np.ascontiguousarray(rank_offsets, dtype=np.int64)
+        if off.shape != (self.p + 1,):
+            raise ValueError("rank_offsets must have p+1 entries")
+        _check(lib().gg_shuffle_noalloc(self._h, step, mode, _dev_ptr(idx, torch.int32, "idx"),
+                                        off.ctypes.data_as(ctypes.c_void_p), batch, _stream_ptr(stream)),
+               "gg_shuffle_noalloc")
 
     def shuffle_payload(self, step, payload, rank_offsets, batch, stream=None):
         """gg_shuffle_payload: payload is a 2-D CUDA tensor [n_total][sample elements]."""

@@ -162,6 +162,8 @@ extern "C" int gg_init(const gg_config* cfg, gg_ctx** out) {
     rc = GG_ERR_HIP;
   } else {
     ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // failure here only disables gg_shuffle_noalloc on this device (it then returns GG_ERR_HIP)
+    (void)gg_static_scratch_setup(ctx->device);
     if (hipMalloc((void**)&ctx->d_sigma, entries * sizeof(uint16_t)) != hipSuccess) {
       rc = GG_ERR_NOMEM;
     } else if (hipMemcpy(ctx->d_sigma, ctx->sigma.data(), entries * sizeof(uint16_t), hipMemcpyHostToDevice) !=
@@ -234,6 +236,7 @@ extern "C" const char* gg_strerror(int code) {
     case GG_ERR_HIP: return "HIP runtime error";
     case GG_ERR_NOMEM: return "out of memory";
     case GG_ERR_UNSUPPORTED: return "not supported";
+    case GG_ERR_LIMIT: return "size exceeds the fixed scratch of the non-allocating entry point";
     default: return "unknown error";
   }
 }

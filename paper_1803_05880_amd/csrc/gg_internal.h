@@ -124,6 +124,10 @@ __host__ __device__ inline gg_u32x4 gg_philox4x32_10(uint32_t c0, uint32_t c1, u
 
 enum { GG_TAG_COMM = 1, GG_TAG_SHUF = 2 };
 
+// Resolves, once per device and with that device current, the device address of the static
+// scratch array that gg_shuffle_noalloc uses (gg_shuffle.hip); called by gg_init.
+int gg_static_scratch_setup(int device);
+
 // Validation helpers (gg_ctx.hip)
 int gg_check_ctx_device(const gg_ctx* ctx);
 inline bool gg_is_pow2(int64_t x) { return x >= 1 && (x & (x - 1)) == 0; }

@@ -2,7 +2,23 @@
 // the partner-swap variant.  Integer work only; results are bit-exact.
 #include <string.h>
 
+#include <mutex>
+
 #include "gg_internal.h"
+
+// ---- scratch that is never allocated: gg_shuffle_noalloc
+// One array per GPU, part of the loaded code object, kept until the process ends.  In host
+// code the array's name is only a stand-in for the symbol: its device address on each GPU
+// comes from hipGetSymbolAddress with that GPU current, and only that address is ever
+// handed to a kernel.  Layout: rank offsets int64[GG_MAX_RANKS + 1] (padded to 256-byte
+// multiple), then the int32 words of check_shuffle's layout.
+enum {
+  NOALLOC_OFF_BYTES = ((GG_MAX_RANKS + 1) * 8 + 255) / 256 * 256,
+  NOALLOC_WORDS = GG_NOALLOC_MAX_INDICES + GG_NOALLOC_MAX_TILE_COUNTS + 4,
+  NOALLOC_MAX_DEVICES = 64,
+  OFFSETS_PER_LAUNCH = 256
+};
+static __device__ __align__(256) unsigned char scratch[NOALLOC_OFF_BYTES + (size_t)NOALLOC_WORDS * 4];
 
 namespace {
 
@@ -351,10 +367,16 @@ int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s, int64_t scratch_word
   return GG_OK;
 }
 
-}  // namespace
+// Argument checks shared by both index-shuffle entry points; fills the per-call sizes.
+struct shuffle_sizes {
+  int64_t min_n, max_n, n_total;
+  int32_t max_tiles;   // tiles of the largest rank (4096 slots each)
+  int64_t counts_at;   // word offset of the per-tile counts behind the flagged-slot lists
+  int64_t words;       // scratch words needed in all
+};
 
-extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx, const int64_t* rank_offsets,
-                          int32_t batch, void* stream) {
+int check_shuffle(const gg_ctx* ctx, int64_t step, int32_t mode, const int32_t* idx, const int64_t* rank_offsets,
+                  int32_t batch, shuffle_sizes* out) {
   if (!ctx || !idx || !rank_offsets || step < 0) return GG_ERR_ARG;
   if (mode != GG_SHUF_PARTNER_SWAP && mode != GG_SHUF_RING) return GG_ERR_ARG;
   if (!gg_aligned(idx, 4)) return GG_ERR_ALIGN;
@@ -373,40 +395,47 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
   } else {
     if (batch < 0 || batch > min_n) return GG_ERR_ARG;
   }
-  int rc = gg_check_ctx_device(ctx);
-  if (rc != GG_OK) return rc;
-  if (rank_offsets[p] == 0) return GG_OK;
-  hipStream_t s = (hipStream_t)stream;
-  // scratch: flagged-slot lists (one word per slot at most), then per-tile counts
   const int64_t per_tile = (int64_t)SWAP_THREADS * SLOTS_PER_THREAD;
-  const int32_t max_tiles = (int32_t)((max_n + per_tile - 1) / per_tile);
-  const int64_t counts_at = (rank_offsets[p] + 3) / 4 * 4;
-  rc = prepare(ctx, rank_offsets, s, counts_at + (int64_t)p * (max_tiles > 0 ? max_tiles : 1));
-  if (rc != GG_OK) return rc;
+  out->min_n = min_n;
+  out->max_n = max_n;
+  out->n_total = rank_offsets[p];
+  out->max_tiles = (int32_t)((max_n + per_tile - 1) / per_tile);
+  // scratch: flagged-slot lists (one word per slot at most; the ring's staged batches fit the
+  // same words, p * batch <= n_total), then per-tile counts
+  out->counts_at = (rank_offsets[p] + 3) / 4 * 4;
+  out->words = out->counts_at + (int64_t)p * (out->max_tiles > 0 ? out->max_tiles : 1);
+  return gg_check_ctx_device(ctx);
+}
 
+// The launches of one index shuffle; d_off and scratch are ready on stream s.
+int enqueue_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx, int32_t batch, const shuffle_sizes& sz,
+                    const int64_t* d_off, int32_t* scratch, hipStream_t s) {
+  const int32_t p = ctx->cfg.p;
   if (mode == GG_SHUF_PARTNER_SWAP) {
     const int32_t k = (int32_t)(step % ctx->L);
     const int32_t r = (int32_t)((step / ctx->L) % ctx->R);
     swap_args a;
     a.idx = idx;
-    a.sel = ctx->d_scratch;
-    a.off = ctx->d_offsets;
+    a.sel = scratch;
+    a.off = d_off;
     a.sigma = ctx->d_sigma + (size_t)r * p;
     a.shift = int32_t(1) << k;
     a.step32 = (uint32_t)((uint64_t)step & 0xffffffffu);
     a.k0 = (uint32_t)ctx->cfg.seed;
     a.k1 = (uint32_t)(ctx->cfg.seed >> 32);
-    if (max_tiles <= 8) {
+    if (sz.max_tiles <= 8) {
       // few tiles per rank: one workgroup per pair does everything in one launch
       hipLaunchKernelGGL(partner_swap_kernel, dim3(p / 2), dim3(SWAP_THREADS), 0, s, a);
       GG_HIP_TRY(hipGetLastError());
     } else {
-      uint32_t* counts = reinterpret_cast<uint32_t*>(ctx->d_scratch + counts_at);
+      // every (tile, rank) count is written by swap_count_kernel before it is read: nothing to clear
+      uint32_t* counts = reinterpret_cast<uint32_t*>(scratch + sz.counts_at);
+      const int32_t max_tiles = sz.max_tiles;
       hipLaunchKernelGGL(swap_count_kernel, dim3(max_tiles, p), dim3(SWAP_THREADS), 0, s, a, counts, max_tiles);
       GG_HIP_TRY(hipGetLastError());
       hipLaunchKernelGGL(swap_scatter_kernel, dim3(max_tiles, p), dim3(SWAP_THREADS), 0, s, a, counts, max_tiles);
       GG_HIP_TRY(hipGetLastError());
-      int64_t bx = max_n / (8 * SWAP_THREADS) + 1;  // about one thread per expected swap
+      int64_t bx = sz.max_n / (8 * SWAP_THREADS) + 1;  // about one thread per expected swap
       if (bx > 4096) bx = 4096;
       hipLaunchKernelGGL(swap_apply_kernel, dim3((unsigned)bx, p / 2), dim3(SWAP_THREADS), 0, s, a, counts, max_tiles);
       GG_HIP_TRY(hipGetLastError());
@@ -415,9 +444,9 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
     if (batch == 0) return GG_OK;
     ring_args a;
     a.idx = idx;
-    a.stage = ctx->d_scratch;
+    a.stage = scratch;
     a.head = nullptr;
-    a.off = ctx->d_offsets;
+    a.off = d_off;
     a.step = step;
     a.batch = batch;
     a.p = p;
@@ -429,6 +458,71 @@ extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx,
     GG_HIP_TRY(hipGetLastError());
   }
   return GG_OK;
+}
+
+std::mutex g_scratch_lock;
+unsigned char* g_scratch_ptr[NOALLOC_MAX_DEVICES];  // per device: address of its copy of `scratch`, or null
+
+// Rank offsets travel to the device in the kernel arguments, 256 at a time: no staging
+// buffer, no copy engine, nothing to allocate.
+struct offsets_block {
+  int64_t v[OFFSETS_PER_LAUNCH];
+};
+__global__ void __launch_bounds__(OFFSETS_PER_LAUNCH) put_offsets_kernel(offsets_block b, int32_t base, int32_t count,
+                                                                         int64_t* dst) {
+  const int32_t i = threadIdx.x;
+  if (i < count) dst[base + i] = b.v[i];
+}
+
+}  // namespace
+
+int gg_static_scratch_setup(int device) {
+  if (device < 0 || device >= NOALLOC_MAX_DEVICES) return GG_ERR_ARG;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (g_scratch_ptr[device]) return GG_OK;
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+    (void)hipGetLastError();
+    return GG_ERR_HIP;
+  }
+  g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+  return GG_OK;
+}
+
+extern "C" int gg_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx, const int64_t* rank_offsets,
+                          int32_t batch, void* stream) {
+  shuffle_sizes sz;
+  int rc = check_shuffle(ctx, step, mode, idx, rank_offsets, batch, &sz);
+  if (rc != GG_OK) return rc;
+  if (sz.n_total == 0) return GG_OK;
+  hipStream_t s = (hipStream_t)stream;
+  rc = prepare(ctx, rank_offsets, s, sz.words);
+  if (rc != GG_OK) return rc;
+  return enqueue_shuffle(ctx, step, mode, idx, batch, sz, ctx->d_offsets, ctx->d_scratch, s);
+}
+
+extern "C" int gg_shuffle_noalloc(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx, const int64_t* rank_offsets,
+                                  int32_t batch, void* stream) {
+  shuffle_sizes sz;
+  int rc = check_shuffle(ctx, step, mode, idx, rank_offsets, batch, &sz);
+  if (rc != GG_OK) return rc;
+  const int32_t p = ctx->cfg.p;
+  if (sz.n_total > GG_NOALLOC_MAX_INDICES) return GG_ERR_LIMIT;
+  if ((int64_t)p * sz.max_tiles > GG_NOALLOC_MAX_TILE_COUNTS) return GG_ERR_LIMIT;
+  if (sz.n_total == 0) return GG_OK;
+  unsigned char* base = ctx->device < NOALLOC_MAX_DEVICES ? g_scratch_ptr[ctx->device] : nullptr;
+  if (!base) return GG_ERR_HIP;  // gg_init could not resolve the array on this device
+  hipStream_t s = (hipStream_t)stream;
+  int64_t* d_off = reinterpret_cast<int64_t*>(base);
+  int32_t* words = reinterpret_cast<int32_t*>(base + NOALLOC_OFF_BYTES);
+  for (int32_t at = 0; at <= p; at += OFFSETS_PER_LAUNCH) {
+    offsets_block b;
+    const int32_t count = p + 1 - at < OFFSETS_PER_LAUNCH ? p + 1 - at : OFFSETS_PER_LAUNCH;
+    for (int32_t i = 0; i < OFFSETS_PER_LAUNCH; ++i) b.v[i] = i < count ? rank_offsets[at + i] : 0;
+    hipLaunchKernelGGL(put_offsets_kernel, dim3(1), dim3(OFFSETS_PER_LAUNCH), 0, s, b, at, count, d_off);
+    GG_HIP_TRY(hipGetLastError());
+  }
+  return enqueue_shuffle(ctx, step, mode, idx, batch, sz, d_off, words, s);
 }
 
 extern "C" int gg_shuffle_payload(gg_ctx* ctx, int64_t step, void* payload, int64_t sample_bytes,
