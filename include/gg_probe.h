@@ -16,6 +16,11 @@
 extern "C" {
 #endif
 
+/* Digest (sha256, hex) of the sources and compiler flags this library was built from,
+ * as the build step computed it; "unknown" for a build that did not pass one.  Lets a
+ * benchmark refuse to time a library that is older than the sources beside it.  Static. */
+const char* gg_build_id(void);
+
 /* Plain device-to-device copy kernel (16-byte non-temporal loads/stores) used to
  * calibrate achievable memory bandwidth next to the gossip kernel, and as the
  * known-size reference that scales the profiler's byte counters.  dst, src:
@@ -30,14 +35,14 @@ int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream);
  * alive).  1 <= blocks <= 65536, iters >= 0. */
 int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream);
 
-/* The same stand-in with memory traffic: `blocks` workgroups of 256 threads stream
- * once over buf (read 16 bytes, run a dependent chain of `iters` multiply-adds on
- * them, write 16 bytes back in place), so the computation competes with the exchange
- * for memory bandwidth the way a forward/backward pass does.  Its share of the
- * bandwidth is set by iters (more arithmetic per byte = lower share) and is measured
- * by the caller.  buf: device, 16-byte aligned, nbytes a multiple of 16; the values
- * written are finite but otherwise meaningless.  1 <= blocks <= 65536, iters >= 0. */
-int gg_stream_probe(int64_t iters, int32_t blocks, void* buf, int64_t nbytes, void* stream);
+/* The same stand-in with memory traffic: one thread per 16 bytes of buf reads them, runs
+ * a dependent chain of `iters` multiply-adds and writes 16 bytes back in place, so the
+ * computation competes with the exchange for memory bandwidth the way a forward/backward
+ * pass does.  Its share of the bandwidth is 2 * nbytes over its duration, which iters
+ * sets (more arithmetic per byte = lower share); the caller measures it.  buf: device,
+ * 16-byte aligned, nbytes a multiple of 16 and below 2^35; what is written is finite but
+ * otherwise meaningless.  iters >= 0. */
+int gg_stream_probe(int64_t iters, void* buf, int64_t nbytes, void* stream);
 
 /* Launch-shape knobs for bandwidth sweeps (never change results). */
 enum {

@@ -7,5 +7,5 @@ from .binding import (  # noqa: F401
     AVG_GRAD, AVG_MODEL, AVG_NONE, Context, GGConfig, GGError, LIB_PATH, MAX_RANKS, SHUF_PARTNER_SWAP,
     SHUF_RING, TOPO_DISSEMINATION, TOPO_HYPERCUBE, TUNE_BLOCKS_PER_CU, TUNE_CHUNKS, TUNE_NONTEMPORAL,
     TUNE_THREADS, TUNE_WALK_BARRIER, TUNE_WALK_CHUNKS, TUNE_WALK_GROUP_LOG2, TUNE_WALK_STEP, TUNE_WALK_WAVES, TUNE_WALK_WG_PER_CU,
-    aligned_stride, busy_probe, copy_probe, lib, stream_probe,
+    aligned_stride, build_id, busy_probe, copy_probe, ensure_current, lib, stream_probe,
 )

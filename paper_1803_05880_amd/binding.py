@@ -86,10 +86,12 @@ def lib():
         L.gg_shuffle_payload.argtypes = [vp, i64, vp, i64, vp, i32, vp]
         L.gg_copy_probe.argtypes = [vp, vp, i64, vp]
         L.gg_busy_probe.argtypes = [i64, i32, vp, vp]
-        L.gg_stream_probe.argtypes = [i64, i32, vp, i64, vp]
+        L.gg_stream_probe.argtypes = [i64, vp, i64, vp]
         L.gg_set_tuning.argtypes = [vp, i32, i32]
         L.gg_strerror.argtypes = [ctypes.c_int]
         L.gg_strerror.restype = ctypes.c_char_p
+        L.gg_build_id.argtypes = []
+        L.gg_build_id.restype = ctypes.c_char_p
         for name in ("gg_init", "gg_destroy", "gg_set_hyper", "gg_partner", "gg_gossip_step", "gg_sgd_step",
                      "gg_allreduce_baseline", "gg_allreduce_onepass", "gg_shuffle", "gg_shuffle_noalloc", "gg_shuffle_payload", "gg_copy_probe",
                      "gg_busy_probe", "gg_stream_probe", "gg_set_tuning"):
@@ -227,7 +229,30 @@ def busy_probe(iters, blocks, sink, stream=None):
            "gg_busy_probe")
 
 
-def stream_probe(iters, blocks, buf, stream=None):
+def stream_probe(iters, buf, stream=None):
     """gg_stream_probe: stand-in for forward/backward computation that also streams memory."""
-    _check(lib().gg_stream_probe(int(iters), int(blocks), ctypes.c_void_p(buf.data_ptr()),
-                                 buf.numel() * buf.element_size(), _stream_ptr(stream)), "gg_stream_probe")
+    _check(lib().gg_stream_probe(int(iters), ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                 _stream_ptr(stream)), "gg_stream_probe")
+
+
+def build_id():
+    """gg_build_id: digest of the sources the loaded library was built from."""
+    return lib().gg_build_id().decode()
+
+
+def ensure_current():
+    """Make sure the library that gets loaded was built from the sources in this tree: a
+    library on disk with another (or no) digest is rebuilt first, as long as it has not been
+    loaded yet.  Returns the digest; raises when the loaded library does not match it."""
+    from .build import DIGEST_PATH, build_library, source_digest
+    digest = source_digest()
+    try:
+        on_disk = open(DIGEST_PATH).read().strip()
+    except OSError:
+        on_disk = None
+    if _lib is None and (on_disk != digest or not os.path.exists(LIB_PATH)):
+        build_library()
+    if build_id() != digest:
+        raise RuntimeError("libgg.so was built from other sources (%s...) than the ones beside it (%s...): run "
+                           "`python -m paper_1803_05880_amd.build`" % (build_id()[:12], digest[:12]))
+    return digest

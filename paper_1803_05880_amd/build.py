@@ -1,5 +1,6 @@
 """Build libgg.so (the C-ABI library) in-tree with hipcc for gfx950."""
 import glob
+import hashlib
 import os
 import subprocess
 import sys
@@ -7,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libgg.so")
+DIGEST_PATH = LIB_PATH + ".digest"      # digest of the sources the library on disk was built from
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
@@ -26,11 +28,25 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
+def source_digest():
+    """sha256 over everything that determines the library: HIP sources, headers, compiler flags.
+    The library reports the digest it was built from (gg_build_id)."""
+    h = hashlib.sha256()
+    h.update("\0".join(HIPCC_FLAGS).encode())
+    files = sources() + sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + \
+        sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    for path in files:
+        h.update(os.path.basename(path).encode() + b"\0")
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
 def build_library(verbose=False):
     """Compile every HIP source into paper_1803_05880_amd/libgg.so.  Always compiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-                                   "-o", LIB_PATH] + sources()
+    digest = source_digest()
+    cmd = [hipcc] + HIPCC_FLAGS + ['-DGG_BUILD_ID="%s"' % digest, "-I", os.path.join(ROOT, "include"),
+                                   "-I", os.path.join(HERE, "csrc"), "-o", LIB_PATH] + sources()
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -39,6 +55,8 @@ def build_library(verbose=False):
         raise RuntimeError("hipcc failed with exit code %d" % res.returncode)
     if verbose and res.stderr.strip():
         sys.stderr.write(res.stderr)
+    with open(DIGEST_PATH, "w") as f:
+        f.write(digest + "\n")
     return LIB_PATH
 
 

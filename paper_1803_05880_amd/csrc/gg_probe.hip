@@ -17,18 +17,23 @@ __global__ void __launch_bounds__(256) busy_kernel(int64_t iters, float* sink) {
 }
 
 // Read 16 bytes, run a dependent chain on them, write them back: arithmetic and memory
-// traffic in a ratio set by iters.
+// traffic in a ratio set by iters.  One chunk per thread, so the traffic is spread evenly
+// over the kernel's duration as the workgroups are dispatched.
 __global__ void __launch_bounds__(256) stream_kernel(int64_t iters, v4f* buf, int64_t count) {
-  const int64_t step = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += step) {
-    v4f x = __builtin_nontemporal_load(buf + i);
-    x = x * 0.0f + 1.0f;  // whatever the buffer held, the chain starts from a finite value
-    for (int64_t k = 0; k < iters; ++k) x = x * 0.999999f + 1e-9f;
-    __builtin_nontemporal_store(x, buf + i);
-  }
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  v4f x = __builtin_nontemporal_load(buf + i);
+  x = x * 0.0f + 1.0f;  // whatever finite values the buffer held, the chain starts from 1
+  for (int64_t k = 0; k < iters; ++k) x = x * 0.999999f + 1e-9f;
+  __builtin_nontemporal_store(x, buf + i);
 }
 
 }  // namespace
+
+#ifndef GG_BUILD_ID
+#define GG_BUILD_ID "unknown"
+#endif
+extern "C" const char* gg_build_id(void) { return GG_BUILD_ID; }
 
 extern "C" int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream) {
   if (!dst || !src || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
@@ -53,12 +58,14 @@ extern "C" int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* s
   return GG_OK;
 }
 
-extern "C" int gg_stream_probe(int64_t iters, int32_t blocks, void* buf, int64_t nbytes, void* stream) {
-  if (!buf || iters < 0 || blocks < 1 || blocks > 65536 || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
+extern "C" int gg_stream_probe(int64_t iters, void* buf, int64_t nbytes, void* stream) {
+  if (!buf || iters < 0 || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
   if (!gg_aligned(buf, 16)) return GG_ERR_ALIGN;
   if (nbytes == 0) return GG_OK;
-  hipLaunchKernelGGL(stream_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, iters, (v4f*)buf,
-                     nbytes / 16);
+  const int64_t count = nbytes / 16;
+  const int64_t blocks = (count + 255) / 256;
+  if (blocks > 0x7fffffffLL) return GG_ERR_ARG;
+  hipLaunchKernelGGL(stream_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, iters, (v4f*)buf, count);
   GG_HIP_TRY(hipGetLastError());
   return GG_OK;
 }
