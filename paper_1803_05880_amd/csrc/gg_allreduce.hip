@@ -106,8 +106,15 @@ struct tree_walk {
     tree_walk<K - 1, B, U>::run(a, ws, idx, on, r + (int64_t(1) << (K - 1)), hi);
 #pragma unroll
     for (int u = 0; u < U; ++u) out[u] = lo[u] + hi[u];
-    // every wavefront of the workgroup passes here once per group of 2^B ranks
-    if (K == B && ws.barrier) __syncthreads();
+    if (K >= B) {
+      // Every sum from a group of 2^B ranks upwards is formed here and now: left alone, the
+      // compiler keeps the values in registers and adds at the very end, which no register
+      // file holds at p = 128.  This way at most one partial sum per tree level is alive.
+#pragma unroll
+      for (int u = 0; u < U; ++u) asm volatile("" : "+v"(out[u]));
+      // every wavefront of the workgroup passes here once per group of 2^B ranks
+      if (K == B && ws.barrier) __syncthreads();
+    }
   }
 };
 template <int B, int U>
@@ -118,7 +125,11 @@ struct tree_walk<0, B, U> {
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (on[u]) out[u] = gg_ld<true>(row + idx[u]);
-    if (B == 0 && ws.barrier) __syncthreads();
+    if (B == 0) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) asm volatile("" : "+v"(out[u]));
+      if (ws.barrier) __syncthreads();
+    }
   }
 };
 
@@ -215,7 +226,7 @@ void launch_walk_u(int U, int K, dim3 grid, dim3 block, uint32_t lds, hipStream_
   if (U == 1)
     launch_walk_k<B, 1>(K, grid, block, lds, s, a, ws);
   else
-    launch_walk_k<B, 2>(K, grid, block, lds, s, a, ws);  // more chunks spill the register stack of partial sums
+    launch_walk_k<B, 2>(K, grid, block, lds, s, a, ws);  // four chunks per thread measured far slower
 }
 
 enum { MAX_ONEPASS_LOG2 = 7 };
@@ -288,8 +299,9 @@ extern "C" int gg_allreduce_onepass(gg_ctx* ctx, float* g, int32_t average, void
   a.scale = 1.0f / (float)ctx->cfg.p;
   if (sp.body.count > 0) {
     a.rng = sp.body;
-    // measured best at p = 64 x 25.6 M parameters: 4 wavefronts x 2 chunks, a barrier every 4 ranks
-    const gg_walk_shape own{2, 4, 32, 0, 1, 2};
+    // measured best at 25.6 M parameters per rank for p = 16, 64 and 128: 4 wavefronts x 1 chunk, 3 workgroups
+    // per CU, a barrier every 4 ranks
+    const gg_walk_shape own{1, 4, 32, 3, 1, 2};
     const gg_walk_launch wl = gg_walk_geometry(ctx, own, 2, (a.rng.count + 63) / 64);
     if (wl.grid_x > 0) {
       walk_shape ws{wl.shape.step, wl.shape.barrier};

@@ -625,8 +625,9 @@ int32_t gcd32(int32_t x, int32_t y) {
 // (nothing enqueued) when the walking form does not apply.
 bool enqueue_walk(const gg_ctx* ctx, int mode, step_args& a, int32_t cycle_len, int64_t cycles,
                   const rank_table& rt, hipStream_t s) {
-  // measured best at p = 64 x 25.6 M parameters: 2 wavefronts x 2 chunks, tiles 32 KB apart, 3 workgroups per CU
-  const gg_walk_shape own{2, 2, 32, 3, 1, 0};
+  // measured best at 25.6 M parameters per rank for p = 16 ... 128 and every cycle length: 4 wavefronts x 1
+  // chunk, tiles 32 KB apart, 3 workgroups per CU
+  const gg_walk_shape own{1, 4, 32, 3, 1, 0};
   const gg_walk_launch wl = gg_walk_geometry(ctx, own, 8, (a.rng.count + 63) / 64);
   if (wl.grid_x == 0) return false;
   walk_args wa;

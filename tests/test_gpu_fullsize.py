@@ -228,3 +228,9 @@ def test_config4_shape_dissemination(staleness, double_buffer):
 def test_config4_shape_gradient_averaging(topology):
     # the gradient-buffer reading of the exchange (Sec. 5) at p = 64 x ResNet50-sized rows
     _run_full(64, 14, checkpoints=(1, 7), topology=topology, avg_mode=gg.AVG_GRAD)
+
+
+def test_config5_shape_dissemination():
+    # p = 128: the longest partner cycle (all 128 ranks at phase 0) down to pairs, 9 steps = every phase and
+    # two steps on a shuffled communicator
+    _run_full(128, 9, checkpoints=(1, 7), topology=gg.TOPO_DISSEMINATION, num_random=32)
