@@ -282,20 +282,23 @@ def layerwise_overlap(torch, gg, gg_synth, ctx, W, G, M, n, gossip_ms, scratch, 
 
     # (2) stand-ins that stream memory while they compute: each piece reads and rewrites a slab
     # of a scratch buffer sized for a stated share of the HBM peak over the piece's duration,
-    # with the arithmetic per byte tuned so that the piece lasts as long as in (1)
+    # with the arithmetic per byte tuned so that the piece lasts as long as in (1).  Like (1)
+    # it runs 1024 workgroups, so the exchange finds wavefront slots beside it.
     out["memory_streaming_compute"] = []
     for duty in (0.25, 0.5):
         slab_bytes = int(duty * HBM_PEAK_GBS * 1e9 * target_piece_ms * 1e-3 / 2) // 4096 * 4096
         slab_bytes = min(slab_bytes, scratch.numel() * 4 // 4096 * 4096)
         slab = scratch.view(-1)[: slab_bytes // 4]
-        t0 = timed(lambda: gg.stream_probe(0, slab), 3)              # pure streaming time of one piece
-        it2 = 0
-        if t0 < target_piece_ms:
-            t1 = timed(lambda: gg.stream_probe(256, slab), 3)
-            per_iter = max(1e-9, (t1 - t0) / 256)
-            it2 = max(0, int((target_piece_ms - t0) / per_iter))
-        piece_ms = timed(lambda: gg.stream_probe(it2, slab), 3)
-        t_c2, t_p2, hid2 = measure(lambda: gg.stream_probe(it2, slab))
+        it2, piece_ms = 0, timed(lambda: gg.stream_probe(0, 1024, slab), 3)    # pure streaming time of one piece
+        if piece_ms < target_piece_ms:
+            it2 = 64
+            for _ in range(8):                                   # arithmetic per chunk until the piece lasts long enough
+                piece_ms = timed(lambda: gg.stream_probe(it2, 1024, slab), 3)
+                if abs(piece_ms - target_piece_ms) < 0.02 * target_piece_ms:
+                    break
+                it2 = max(1, min(it2 * 4, int(it2 * target_piece_ms / piece_ms + 0.5)))
+            piece_ms = timed(lambda: gg.stream_probe(it2, 1024, slab), 3)
+        t_c2, t_p2, hid2 = measure(lambda: gg.stream_probe(it2, 1024, slab))
         out["memory_streaming_compute"].append({
             "target_share_of_hbm_peak": duty, "slab_MB": round(slab_bytes / 1e6, 1),
             "compute_GBps_alone": round(2.0 * slab_bytes / (piece_ms * 1e-3) / 1e9, 1),

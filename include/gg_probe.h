@@ -35,14 +35,15 @@ int gg_copy_probe(void* dst, const void* src, int64_t nbytes, void* stream);
  * alive).  1 <= blocks <= 65536, iters >= 0. */
 int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* stream);
 
-/* The same stand-in with memory traffic: one thread per 16 bytes of buf reads them, runs
- * a dependent chain of `iters` multiply-adds and writes 16 bytes back in place, so the
- * computation competes with the exchange for memory bandwidth the way a forward/backward
- * pass does.  Its share of the bandwidth is 2 * nbytes over its duration, which iters
- * sets (more arithmetic per byte = lower share); the caller measures it.  buf: device,
- * 16-byte aligned, nbytes a multiple of 16 and below 2^35; what is written is finite but
- * otherwise meaningless.  iters >= 0. */
-int gg_stream_probe(int64_t iters, void* buf, int64_t nbytes, void* stream);
+/* The same stand-in with memory traffic: `blocks` workgroups of 256 threads stride once
+ * over buf; a thread reads four 16-byte chunks, runs a dependent chain of `iters`
+ * multiply-adds on each and writes them back in place, so the computation competes with
+ * the exchange for memory bandwidth the way a forward/backward pass does while leaving
+ * it wavefront slots.  Its share of the bandwidth is 2 * nbytes over its duration, which
+ * iters sets (more arithmetic per byte = lower share); the caller measures it.  buf:
+ * device, 16-byte aligned, nbytes a multiple of 16; what is written is finite but
+ * otherwise meaningless.  1 <= blocks <= 65536, iters >= 0. */
+int gg_stream_probe(int64_t iters, int32_t blocks, void* buf, int64_t nbytes, void* stream);
 
 /* Launch-shape knobs for bandwidth sweeps (never change results). */
 enum {

@@ -86,7 +86,7 @@ def lib():
         L.gg_shuffle_payload.argtypes = [vp, i64, vp, i64, vp, i32, vp]
         L.gg_copy_probe.argtypes = [vp, vp, i64, vp]
         L.gg_busy_probe.argtypes = [i64, i32, vp, vp]
-        L.gg_stream_probe.argtypes = [i64, vp, i64, vp]
+        L.gg_stream_probe.argtypes = [i64, i32, vp, i64, vp]
         L.gg_set_tuning.argtypes = [vp, i32, i32]
         L.gg_strerror.argtypes = [ctypes.c_int]
         L.gg_strerror.restype = ctypes.c_char_p
@@ -229,10 +229,10 @@ def busy_probe(iters, blocks, sink, stream=None):
            "gg_busy_probe")
 
 
-def stream_probe(iters, buf, stream=None):
+def stream_probe(iters, blocks, buf, stream=None):
     """gg_stream_probe: stand-in for forward/backward computation that also streams memory."""
-    _check(lib().gg_stream_probe(int(iters), ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
-                                 _stream_ptr(stream)), "gg_stream_probe")
+    _check(lib().gg_stream_probe(int(iters), int(blocks), ctypes.c_void_p(buf.data_ptr()),
+                                 buf.numel() * buf.element_size(), _stream_ptr(stream)), "gg_stream_probe")
 
 
 def build_id():

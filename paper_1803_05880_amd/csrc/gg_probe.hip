@@ -17,15 +17,26 @@ __global__ void __launch_bounds__(256) busy_kernel(int64_t iters, float* sink) {
 }
 
 // Read 16 bytes, run a dependent chain on them, write them back: arithmetic and memory
-// traffic in a ratio set by iters.  One chunk per thread, so the traffic is spread evenly
-// over the kernel's duration as the workgroups are dispatched.
+// traffic in a ratio set by iters.  A fixed number of workgroups strides over the buffer,
+// four chunks per thread in flight, so the stand-in leaves wavefront slots to the kernels
+// it runs beside (as a computation that is not purely memory-bound does).
 __global__ void __launch_bounds__(256) stream_kernel(int64_t iters, v4f* buf, int64_t count) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= count) return;
-  v4f x = __builtin_nontemporal_load(buf + i);
-  x = x * 0.0f + 1.0f;  // whatever finite values the buffer held, the chain starts from 1
-  for (int64_t k = 0; k < iters; ++k) x = x * 0.999999f + 1e-9f;
-  __builtin_nontemporal_store(x, buf + i);
+  const int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += 4 * step) {
+    v4f x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * step < count) x[u] = __builtin_nontemporal_load(buf + i + u * step);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) x[u] = x[u] * 0.0f + 1.0f;  // whatever finite values the buffer held: start from 1
+    for (int64_t k = 0; k < iters; ++k) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) x[u] = x[u] * 0.999999f + 1e-9f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * step < count) __builtin_nontemporal_store(x[u], buf + i + u * step);
+  }
 }
 
 }  // namespace
@@ -58,14 +69,12 @@ extern "C" int gg_busy_probe(int64_t iters, int32_t blocks, float* sink, void* s
   return GG_OK;
 }
 
-extern "C" int gg_stream_probe(int64_t iters, void* buf, int64_t nbytes, void* stream) {
-  if (!buf || iters < 0 || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
+extern "C" int gg_stream_probe(int64_t iters, int32_t blocks, void* buf, int64_t nbytes, void* stream) {
+  if (!buf || iters < 0 || blocks < 1 || blocks > 65536 || nbytes < 0 || nbytes % 16) return GG_ERR_ARG;
   if (!gg_aligned(buf, 16)) return GG_ERR_ALIGN;
   if (nbytes == 0) return GG_OK;
-  const int64_t count = nbytes / 16;
-  const int64_t blocks = (count + 255) / 256;
-  if (blocks > 0x7fffffffLL) return GG_ERR_ARG;
-  hipLaunchKernelGGL(stream_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, iters, (v4f*)buf, count);
+  hipLaunchKernelGGL(stream_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, iters, (v4f*)buf,
+                     nbytes / 16);
   GG_HIP_TRY(hipGetLastError());
   return GG_OK;
 }

@@ -150,10 +150,11 @@ def test_probe_entry_points_validate_arguments():
     assert L.gg_busy_probe(-1, 4, ctypes.c_void_p(256), None) == E.GG_ERR_ARG
     assert L.gg_busy_probe(10, 4, None, None) == E.GG_ERR_ARG
     ctx = gg.Context(p=4, n=8)
-    assert L.gg_stream_probe(10, None, 16, None) == E.GG_ERR_ARG
-    assert L.gg_stream_probe(10, ctypes.c_void_p(256), 24, None) == E.GG_ERR_ARG
-    assert L.gg_stream_probe(10, ctypes.c_void_p(260), 16, None) == E.GG_ERR_ALIGN
-    assert L.gg_stream_probe(10, ctypes.c_void_p(256), 0, None) == 0
+    assert L.gg_stream_probe(10, 4, None, 16, None) == E.GG_ERR_ARG
+    assert L.gg_stream_probe(10, 0, ctypes.c_void_p(256), 16, None) == E.GG_ERR_ARG
+    assert L.gg_stream_probe(10, 4, ctypes.c_void_p(256), 24, None) == E.GG_ERR_ARG
+    assert L.gg_stream_probe(10, 4, ctypes.c_void_p(260), 16, None) == E.GG_ERR_ALIGN
+    assert L.gg_stream_probe(10, 4, ctypes.c_void_p(256), 0, None) == 0
     assert len(L.gg_build_id()) == 64
     assert L.gg_set_tuning(ctx._h, E.TUNE_WALK_CHUNKS, 3) == E.GG_ERR_ARG and L.gg_set_tuning(ctx._h, E.TUNE_WALK_CHUNKS, 0) == 0
     assert L.gg_set_tuning(ctx._h, E.TUNE_WALK_WAVES, 2) == 0

@@ -74,7 +74,7 @@ def test_pipelined_buckets_config3_shape(stand_in):
         piece = lambda: gg.busy_probe(40_000, 1024, sink)
     else:
         slab = torch.zeros(64 * 1024 * 1024, device=DEV)
-        piece = lambda: gg.stream_probe(8, slab)
+        piece = lambda: gg.stream_probe(8, 1024, slab)
     _run_pipelined(ctx, W, G, M, buckets, steps, piece)
     for t in range(steps):
         ctx.gossip_step(t, wb, G, mb)
