@@ -251,24 +251,28 @@ def test_repeated_calls_are_deterministic():
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
-def test_step_can_be_captured_in_a_graph_and_replayed():
-    # the call only enqueues kernels (no allocation, no host state): a captured step replays
-    # to the same bits as eager calls of the same step, replay after replay
-    p, n = 8, 300_000
-    W, G, M = host_state(p, n, n, seed=20)
-    ctx = gg.Context(p=p, n=n, rank_stride=n, seed=20, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM)
+@pytest.mark.parametrize("topology,p,step", [(gg.TOPO_HYPERCUBE, 8, 4), (gg.TOPO_DISSEMINATION, 8, 3),
+                                             (gg.TOPO_DISSEMINATION, 48, 0)])
+def test_step_can_be_captured_in_a_graph_and_replayed(topology, p, step):
+    # the call only enqueues kernels (no allocation, no host state) -- also the very first call of a
+    # context, also a dissemination phase with one long partner cycle: a captured step replays to the
+    # same bits as eager calls of the same step, replay after replay
+    n = 300_003
+    stride = n + 1
+    W, G, M = host_state(p, n, stride, seed=20)
     w, g, m = W.to(DEV), G.to(DEV), M.to(DEV)
     we, me = W.to(DEV), M.to(DEV)
-    ctx.gossip_step(4, we, g, me)                        # eager warm-up on its own buffers
-    we.copy_(w); me.copy_(m)
+    ctx = gg.Context(p=p, n=n, rank_stride=stride, seed=20, lr=gg_synth.LR, momentum=gg_synth.MOMENTUM,
+                     topology=topology)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        ctx.gossip_step(4, w, g, m)
-    w.copy_(W.to(DEV)); m.copy_(M.to(DEV))               # capture does not execute; start from the inputs
+        ctx.gossip_step(step, w, g, m)                   # the context's first call is the captured one
+    torch.cuda.synchronize()
+    assert torch.equal(w.cpu(), W) and torch.equal(m.cpu(), M)      # capture does not execute
     for replay in range(3):
         graph.replay()
-        ctx.gossip_step(4, we, g, me)
+        ctx.gossip_step(step, we, g, me)
         torch.cuda.synchronize()
         assert torch.equal(w, we) and torch.equal(m, me), "replay %d" % replay
     ctx.close()
