@@ -56,7 +56,7 @@ enum {
   /* kernels that walk over many ranks (dissemination cycles, one-pass all-reduce, payload ring); a key
      that was never set keeps each kernel's own default, given as cycles / all-reduce / ring: */
   GG_TUNE_WALK_CHUNKS = 4,   /* chunks per thread: 1, 2, 4, 8 (1 / 1 / 1); 0 = the kernel's general form      */
-  GG_TUNE_WALK_WAVES = 5,    /* wavefronts per workgroup: 1, 2, 4, 8 (4 / 4 / 4); chunks * waves <= 8         */
+  GG_TUNE_WALK_WAVES = 5,    /* wavefronts per workgroup: 1, 2, 4, 8 (4 / 4 / 8); chunks * waves <= 8         */
   GG_TUNE_WALK_STEP = 6,     /* tiles (1 KB) between two tiles of one workgroup: 1..65536 (32)                */
   GG_TUNE_WALK_WG_PER_CU = 7,/* cap on resident workgroups per CU: 0 = none, 3..64 (3 / 3 / 0)                */
   GG_TUNE_WALK_BARRIER = 8,  /* barrier after every hop: 0, 1 (1)                                             */

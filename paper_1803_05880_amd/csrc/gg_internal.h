@@ -90,7 +90,7 @@ struct gg_ctx {
   // shuffle state
   int32_t* d_scratch;           // device int32[scratch_cap]
   int64_t scratch_cap;
-  int64_t* d_offsets;           // device int64[2p+1]: rank offsets, then the ring heads of the current call
+  int64_t* d_offsets;           // device int64[p+1]
   int64_t* h_offsets_pinned;    // pinned staging for the upload
   std::vector<int64_t> offsets_cached;
 };

@@ -201,7 +201,6 @@ struct ring_args {
   int32_t* idx;
   int32_t* stage;      // scratch int32[p * batch]
   const int64_t* off;  // device int64[p+1]
-  int64_t* head;       // device int64[p]: head of every rank's queue at this step, (step*batch) mod n_j
   int64_t step;
   int32_t batch;
   int32_t p;
@@ -215,12 +214,6 @@ __device__ __forceinline__ int64_t ring_head(const ring_args& a, int32_t j) {
 __device__ __forceinline__ int64_t ring_slot(const ring_args& a, int32_t j, int32_t r) {
   const int64_t n_j = a.off[j + 1] - a.off[j];
   return a.off[j] + (ring_head(a, j) + r) % n_j;
-}
-
-// The heads once per call, so that the payload walk below needs no division per hop.
-__global__ void __launch_bounds__(256) ring_heads_kernel(ring_args a) {
-  const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j < a.p) a.head[j] = ring_head(a, j);
 }
 
 // Phase 1: every rank's batch at the head of its queue is copied out.
@@ -266,7 +259,9 @@ __global__ void __launch_bounds__(256) ring_payload_kernel(ring_args a, Wd* payl
 // in memory wherever they fall into one sample, i.e. in the same DRAM channel.  It takes
 // the ranks D at a time: D loads per word in flight, then the D stores (every store
 // follows the load of the same address in program order), then a barrier, so that
-// only D ranks' batches are streamed at a time instead of all p.
+// only D ranks' batches are streamed at a time instead of all p.  The queue heads
+// ((step*batch) mod n_j: three 64-bit divisions) are worked out once per workgroup into
+// LDS, so a hop costs no division.
 struct ring_walk_shape {
   int32_t step;
   int32_t barrier;
@@ -291,10 +286,13 @@ __global__ void __launch_bounds__(512 / U) ring_payload_walk_kernel(ring_args a,
       x[u] = t - (int64_t)r[u] * words;
     }
   }
+  __shared__ int64_t s_head[GG_MAX_RANKS];
+  for (int32_t j = threadIdx.x; j < a.p; j += blockDim.x) s_head[j] = ring_head(a, j);
+  __syncthreads();
   // word of batch entry r[u] in rank j: head + r < 2 n_j, so one conditional subtraction wraps it
   auto word_at = [&](int32_t j, int u) -> v4f* {
     const int64_t off_j = a.off[j], n_j = a.off[j + 1] - off_j;
-    int64_t slot = a.head[j] + r[u];
+    int64_t slot = s_head[j] + r[u];
     if (slot >= n_j) slot -= n_j;
     return payload + (off_j + slot) * words + x[u];
   };
@@ -337,7 +335,7 @@ __global__ void __launch_bounds__(512 / U) ring_payload_walk_kernel(ring_args a,
 int prepare(gg_ctx* ctx, const int64_t* off, hipStream_t s, int64_t scratch_words) {
   const int32_t p = ctx->cfg.p;
   if (!ctx->d_offsets) {
-    if (hipMalloc((void**)&ctx->d_offsets, (size_t)(2 * p + 1) * sizeof(int64_t)) != hipSuccess ||  // + p heads
+    if (hipMalloc((void**)&ctx->d_offsets, (size_t)(p + 1) * sizeof(int64_t)) != hipSuccess ||
         hipHostMalloc((void**)&ctx->h_offsets_pinned, (size_t)(p + 1) * sizeof(int64_t), hipHostMallocDefault) !=
             hipSuccess) {
       (void)hipGetLastError();
@@ -445,8 +443,7 @@ int enqueue_shuffle(gg_ctx* ctx, int64_t step, int32_t mode, int32_t* idx, int32
     ring_args a;
     a.idx = idx;
     a.stage = scratch;
-    a.head = nullptr;
-    a.off = d_off;
+      a.off = d_off;
     a.step = step;
     a.batch = batch;
     a.p = p;
@@ -548,20 +545,16 @@ extern "C" int gg_shuffle_payload(gg_ctx* ctx, int64_t step, void* payload, int6
   ring_args a;
   a.idx = nullptr;
   a.stage = nullptr;
-  a.head = nullptr;
   a.off = ctx->d_offsets;
   a.step = step;
   a.batch = batch;
   a.p = p;
   const bool vec = gg_aligned(payload, 16) && sample_bytes % 16 == 0;
   const int64_t words = vec ? sample_bytes / 16 : sample_bytes / 4;
-  // measured best for 64 ranks x 32 samples of 192 KB: 4 wavefronts x 1 chunk, 2 ranks per barrier, no cap
-  const gg_walk_shape own{1, 4, 32, 0, 1, 1};
+  // measured best for 64 ranks x 32 samples of 192 KB: 8 wavefronts x 1 chunk, 2 ranks per barrier, no cap
+  const gg_walk_shape own{1, 8, 32, 0, 1, 1};
   const gg_walk_launch wl = gg_walk_geometry(ctx, own, 4, ((int64_t)batch * words + 63) / 64);
   if (vec && wl.grid_x > 0) {
-    a.head = ctx->d_offsets + (p + 1);
-    hipLaunchKernelGGL(ring_heads_kernel, dim3((p + 255) / 256), dim3(256), 0, s, a);
-    GG_HIP_TRY(hipGetLastError());
     ring_walk_shape ws{wl.shape.step, wl.shape.barrier};
     const uint32_t lds = wl.lds_bytes;
     const int U = wl.shape.chunks;
