@@ -58,7 +58,7 @@ __device__ __forceinline__ int64_t gg_item_index(const gg_range& r, int64_t x) {
 
 // Workgroup shape of a kernel that walks over many ranks (dissemination cycles, one-pass
 // all-reduce, payload ring).  In gg_tuning a field of GG_WALK_UNSET means "the kernel's own
-// default"; gg_walk_resolve fills those in.
+// default"; gg_walk_geometry fills those in.
 enum { GG_WALK_UNSET = -1 };
 struct gg_walk_shape {
   int32_t chunks;      // 16-byte chunks per thread (1, 2, 4, 8); 0: the kernel's general form instead
@@ -138,7 +138,8 @@ struct gg_grid {
   dim3 grid;
   dim3 block;
   int64_t tiles;       // tiles per row
-  uint32_t lds_bytes;  // dynamic LDS reserved only to cap the workgroups resident on a CU
+  uint32_t lds_bytes;  // dynamic LDS reserved only to cap the workgroups resident on a CU; the kernels launched
+                       // with it use no LDS of their own, so the cap is exactly what the reservation says
 };
 // `loads` = 16-byte loads one thread keeps in flight; the occupancy cap is stated for the
 // pair kernel (6 loads per thread) and scaled so that every kernel keeps about the same
@@ -151,7 +152,8 @@ gg_grid gg_make_grid(const gg_ctx* ctx, int64_t items, int32_t chunks, int64_t r
 struct gg_walk_launch {
   gg_walk_shape shape;  // defaults resolved, chunks clamped to max_chunks
   int64_t grid_x;       // 0 when the walking form does not apply (chunks == 0 or the grid would not fit)
-  uint32_t lds_bytes;   // LDS reserved (never touched) to cap the resident workgroups per CU
+  uint32_t lds_bytes;   // LDS reserved (never touched) to cap the resident workgroups per CU; a kernel that
+                        // also has static LDS (the payload ring: 8 KB of queue heads) fits fewer than asked
 };
 gg_walk_launch gg_walk_geometry(const gg_ctx* ctx, const gg_walk_shape& kernel_default, int32_t max_chunks,
                                 int64_t tiles);
