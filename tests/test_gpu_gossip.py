@@ -92,7 +92,7 @@ def test_variants_hypercube(mode, p, n, stride):
 @pytest.mark.parametrize("mode", [dict(), dict(staleness=1), dict(avg_mode=gg.AVG_GRAD),
                                   dict(staleness=1, double_buffer=True), dict(double_buffer=True)])
 @pytest.mark.parametrize("p,n,stride", [(8, 300_007, 300_008), (6, 50_001, 50_004), (5, 4097, 4097), (2, 1000, 1000),
-                                        (16, 33_000, 33_000)])
+                                        (16, 33_000, 33_000), (3, 70_000, 70_000)])
 def test_dissemination_data_path(mode, p, n, stride):
     _check(p, n, stride, 2 * sc.num_phases(p) + 2, seed=6, topology=gg.TOPO_DISSEMINATION, **mode)
 

@@ -94,7 +94,7 @@ def test_shuffle_argument_errors():
     ctx.close()
 
 
-@pytest.mark.parametrize("p,n_total,batch,sample_words", [(3, 12, 2, 4), (4, 64, 4, 12), (8, 1000, 17, 5),
+@pytest.mark.parametrize("p,n_total,batch,sample_words", [(2, 10, 3, 8), (3, 12, 2, 4), (4, 64, 4, 12), (8, 1000, 17, 5),
                                                           (16, 4096, 32, 3072), (128, 128 * 40, 32, 1024)])
 def test_ring_payload_bit_exact_and_glued_to_indices(p, n_total, batch, sample_words):
     off = sh.block_offsets(n_total, p)
