@@ -234,3 +234,29 @@ def test_config5_shape_dissemination():
     # p = 128: the longest partner cycle (all 128 ranks at phase 0) down to pairs, 9 steps = every phase and
     # two steps on a shuffled communicator
     _run_full(128, 9, checkpoints=(1, 7), topology=gg.TOPO_DISSEMINATION, num_random=32)
+
+
+@pytest.mark.parametrize("p", [64, 128])
+def test_allreduce_forms_at_full_size(p):
+    # the comparator at p = 64 and p = 128 x ResNet50-sized rows: the one-pass walk (a register stack of
+    # log2 p partial sums) and the L rounds give the same bits over the whole buffer, and the oracle's on
+    # sampled windows; every rank ends with the same gradient
+    n = gg_synth.RESNET50_PARAMS
+    stride = _bench_stride(n)
+    gen = torch.Generator(device=DEV).manual_seed(p)
+    G = torch.zeros((p, stride), device=DEV)
+    G[:, :n].normal_(0.0, gg_synth.G_STD, generator=gen)
+    cols = _columns(n, 32)
+    cd = torch.as_tensor(cols, device=DEV)
+    Go = _take(G, cd)
+    ctx = gg.Context(p=p, n=n, rank_stride=stride)
+    g1, g2 = G.clone(), G
+    ctx.allreduce_onepass(g1, average=True)
+    ctx.allreduce_baseline(g2, average=True)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, g2)
+    assert torch.equal(g1[0], g1[p - 1]) and torch.equal(g1[0], g1[p // 2])
+    assert torch.count_nonzero(g1[:, n:]) == 0
+    og.allreduce_recursive_doubling(Go, average=True)
+    assert assert_close_fp32(_take(g1, cd), Go, "G") == 0
+    ctx.close()
